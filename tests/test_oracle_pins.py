@@ -1,0 +1,427 @@
+"""Pins of the CPU oracle against things other than itself: closed forms, torch
+library routines, brute force, and the invariants the paper states.  CPU only."""
+import math
+import os
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cacheblend_oracle as O
+from workloads import synth
+from workloads.configs import ModelShape, Workload, WORKLOADS
+
+import ref_torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+SMALL = ModelShape(n_layers=3, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ff=48,
+                   rms_eps=1e-5, rope_theta=100.0, dtype="f32")
+SMALL_W = Workload("small", SMALL, (5, 7, 6), 3, 0.3, 0.5, 11, 12)
+
+
+def make(w: Workload, std=None):
+    layers = synth.model_weights(w.model, w.seed_weights)
+    if std is not None:  # larger weights make attention far from uniform
+        for lw in layers:
+            for k in lw:
+                if k.startswith("w"):
+                    lw[k] = lw[k] * (std / synth.WEIGHT_STD)
+    x = synth.hidden_inputs(w)
+    np_layers = [{k: synth.to_f64(v) for k, v in lw.items()} for lw in layers]
+    return layers, np_layers, x, synth.to_f64(x)
+
+
+# ------------------------------------------------------------------ RoPE ----
+def test_rope_matches_paper_2d_rotation_fixture():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "rope_2d.txt")) if l[0] not in "#\n"]
+    assert len(rows) >= 5
+    for m_, v0, v1, e0, e1 in rows:
+        got = O.rope(np.array([[[float(v0), float(v1)]]]), [int(m_)], theta=1e4)
+        np.testing.assert_allclose(got[0, 0], [float(e0), float(e1)], rtol=0, atol=1e-15)
+
+
+def test_rope_equals_complex_multiplication():
+    rng = np.random.default_rng(0)
+    v = rng.standard_normal((9, 3, 16))
+    pos = np.array([0, 1, 2, 5, 17, 100, 1000, 4095, 32767])
+    got = O.rope(v, pos, 1e6)
+    ref = ref_torch.rope_complex(torch.from_numpy(v), torch.from_numpy(pos), 1e6).numpy()
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+def test_rope_frequencies_closed_form():
+    f = O.rope_frequencies(8, 10000.0)
+    np.testing.assert_allclose(f, [1.0, 0.1, 0.01, 0.001], rtol=1e-14)
+
+
+def test_rope_rotations_add_and_keep_norm():          # R(a)R(b) = R(a+b)
+    rng = np.random.default_rng(1)
+    v = rng.standard_normal((4, 2, 32))
+    a, b = np.array([3, 0, 511, 20000]), np.array([7, 12, 512, 12000])
+    np.testing.assert_allclose(O.rope(O.rope(v, a, 1e4), b, 1e4), O.rope(v, a + b, 1e4), atol=1e-9)
+    np.testing.assert_allclose(np.linalg.norm(O.rope(v, a, 1e4), axis=-1),
+                               np.linalg.norm(v, axis=-1), rtol=1e-12)
+
+
+def test_rope_score_depends_on_relative_position_only():   # Appendix A proposition
+    rng = np.random.default_rng(2)
+    q, k = rng.standard_normal((1, 1, 64)), rng.standard_normal((1, 1, 64))
+    l = 37
+    scores = [float(np.sum(O.rope(q, [m_ + l], 1e4) * O.rope(k, [m_], 1e4))) for m_ in (0, 5, 900, 31000)]
+    np.testing.assert_allclose(scores, scores[0], rtol=0, atol=1e-9)
+    # and it is NOT independent of l
+    other = float(np.sum(O.rope(q, [l + 1], 1e4) * O.rope(k, [0], 1e4)))
+    assert abs(other - scores[0]) > 1e-3
+
+
+def test_realigned_keys_equal_keys_computed_at_new_positions():
+    layers, npl, x, xn = make(SMALL_W)
+    m = SMALL
+    # layer-0 keys of chunk 1 cached at 0.. vs computed directly at o_1 ..
+    lens = SMALL_W.chunk_lens
+    kpre, vpre = O.chunk_prefill(xn[:SMALL_W.n_ctx], lens, npl[:1], m)
+    re = O.realign_keys(kpre[0], lens, m)
+    _, k_direct, _ = O.project_kv(xn[:SMALL_W.n_ctx], np.arange(SMALL_W.n_ctx), O.as_f64_weights(npl[0]), m)
+    np.testing.assert_allclose(re, k_direct, atol=1e-12)
+    # chunk 0 untouched bit for bit
+    assert np.array_equal(re[:lens[0]], kpre[0][:lens[0]])
+
+
+# ------------------------------------------------------- block pieces -------
+def test_rmsnorm_silu_bf16_against_torch():
+    rng = np.random.default_rng(3)
+    x, g = rng.standard_normal((6, 40)), rng.standard_normal(40)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x), (40,), torch.from_numpy(g), 1e-5).numpy()
+    np.testing.assert_allclose(O.rms_norm(x, g, 1e-5), ref, rtol=1e-13)
+    np.testing.assert_allclose(O.silu(x), torch.nn.functional.silu(torch.from_numpy(x)).numpy(), rtol=1e-13)
+    y = rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))
+    y[:4] = [1.00390625, 1.01171875, -0.0, 3.3895313892515355e38]  # two exact ties, signed zero, near max
+    ref = torch.from_numpy(y.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.round_bf16(y)
+    finite = np.isfinite(ref)
+    assert np.array_equal(got[finite], ref[finite])
+
+
+def test_attention_against_torch_sdpa_and_sparse_rows():
+    rng = np.random.default_rng(4)
+    T, hq, hkv, dh = 23, 4, 2, 8
+    q, k, v = rng.standard_normal((T, hq, dh)), rng.standard_normal((T, hkv, dh)), rng.standard_normal((T, hkv, dh))
+    tq, tk, tv = (torch.from_numpy(a).transpose(0, 1) for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        tq, tk.repeat_interleave(2, 0), tv.repeat_interleave(2, 0), is_causal=True).transpose(0, 1).numpy()
+    got = O.attention(q, np.arange(T), k, v)
+    np.testing.assert_allclose(got, ref, atol=1e-12)
+    rows = np.array([0, 3, 4, 11, 22])
+    np.testing.assert_allclose(O.attention(q[rows], rows, k, v), ref[rows], atol=1e-12)
+
+
+def brute_layer(h, lw, m, pos):
+    """One decoder layer with explicit loops and an explicit n x n masked matrix,
+    GQA expanded to one kv head per query head (tiny shapes only)."""
+    n, d = len(h), m.d_model
+    dh, g = m.head_dim, m.n_q_heads // m.n_kv_heads
+
+    def matvec(w, x):  # w [out][in]
+        return [sum(w[o][i] * x[i] for i in range(len(x))) for o in range(len(w))]
+
+    def norm(x, gain):
+        ms = sum(t * t for t in x) / len(x)
+        return [t / math.sqrt(ms + m.rms_eps) * gg for t, gg in zip(x, gain)]
+
+    def rot(vec, p):
+        out = list(vec)
+        for hd in range(len(vec) // dh):
+            for i in range(dh // 2):
+                th = m.rope_theta ** (-2.0 * i / dh)
+                a, b = vec[hd * dh + 2 * i], vec[hd * dh + 2 * i + 1]
+                out[hd * dh + 2 * i] = a * math.cos(p * th) - b * math.sin(p * th)
+                out[hd * dh + 2 * i + 1] = a * math.sin(p * th) + b * math.cos(p * th)
+        return out
+
+    xs = [norm(list(r), lw["attn_norm"]) for r in h]
+    qs = [rot(matvec(lw["wq"], x), p) for x, p in zip(xs, pos)]
+    ks = [rot(matvec(lw["wk"], x), p) for x, p in zip(xs, pos)]
+    vs = [matvec(lw["wv"], x) for x in xs]
+    out_rows = []
+    for t in range(n):
+        o = []
+        for hq in range(m.n_q_heads):
+            kv = hq // g
+            sc = [sum(qs[t][hq * dh + e] * ks[j][kv * dh + e] for e in range(dh)) / math.sqrt(dh)
+                  if j <= t else None for j in range(n)]
+            mx = max(s for s in sc if s is not None)
+            w_ = [math.exp(s - mx) if s is not None else 0.0 for s in sc]
+            z = sum(w_)
+            o += [sum(w_[j] / z * vs[j][kv * dh + e] for j in range(n)) for e in range(dh)]
+        hmid = [a + b for a, b in zip(h[t], matvec(lw["wo"], o))]
+        y = norm(hmid, lw["mlp_norm"])
+        gate, up = matvec(lw["w_gate"], y), matvec(lw["w_up"], y)
+        act = [a / (1 + math.exp(-a)) * b for a, b in zip(gate, up)]
+        out_rows.append([a + b for a, b in zip(hmid, matvec(lw["w_down"], act))])
+    return np.array(out_rows), np.array(ks), np.array(vs)
+
+
+def test_full_prefill_against_brute_force_loops():
+    m = ModelShape(2, 8, 4, 2, 4, 12, 1e-5, 50.0, "f32")
+    w = Workload("bf", m, (6,), 2, 1.0, 1.0, 5, 6)
+    _, npl, _, xn = make(w, std=0.5)
+    ks, vs, hfin = O.full_prefill(xn, npl, m)
+    h = xn
+    for l, lw in enumerate(npl):
+        h, bk, bv = brute_layer(h.tolist(), {k: v.tolist() for k, v in lw.items()}, m, list(range(len(xn))))
+        np.testing.assert_allclose(ks[l].reshape(len(xn), -1), bk, atol=1e-12)
+        np.testing.assert_allclose(vs[l].reshape(len(xn), -1), bv, atol=1e-12)
+    np.testing.assert_allclose(hfin, h, atol=1e-11)
+
+
+def test_full_prefill_against_torch_library_composition():
+    layers, npl, x, xn = make(SMALL_W, std=0.3)
+    ks, vs, hfin = O.full_prefill(xn, npl, SMALL)
+    rk, rv, rh = ref_torch.full_prefill(x, layers, SMALL)
+    for l in range(SMALL.n_layers):
+        np.testing.assert_allclose(ks[l], rk[l].numpy(), atol=1e-11)
+        np.testing.assert_allclose(vs[l], rv[l].numpy(), atol=1e-11)
+    np.testing.assert_allclose(hfin, rh.numpy(), atol=1e-10)
+    # chunk prefill at position 0: chunk c of KV^pre == a prefill of that chunk alone
+    kpre, vpre = O.chunk_prefill(xn[:SMALL_W.n_ctx], SMALL_W.chunk_lens, npl, SMALL)
+    o = SMALL_W.chunk_lens[0]
+    ck, cv, _ = ref_torch.full_prefill(x[o:o + SMALL_W.chunk_lens[1]], layers, SMALL)
+    for l in range(SMALL.n_layers):
+        np.testing.assert_allclose(kpre[l][o:o + SMALL_W.chunk_lens[1]], ck[l].numpy(), atol=1e-11)
+        np.testing.assert_allclose(vpre[l][o:o + SMALL_W.chunk_lens[1]], cv[l].numpy(), atol=1e-11)
+
+
+# ------------------------------------------------------------ selection -----
+def brute_topk(dev, k):
+    n = len(dev)
+    keep = []
+    for i in range(n):
+        rank = sum(1 for j in range(n) if dev[j] > dev[i] or (dev[j] == dev[i] and j < i))
+        if rank < k:
+            keep.append(i)
+    return keep
+
+
+@pytest.mark.parametrize("n,k", [(1, 0), (1, 1), (17, 0), (17, 17), (17, 5), (64, 13), (200, 60)])
+def test_top_k_against_rank_counting(n, k):
+    rng = np.random.default_rng(n * 31 + k)
+    dev = rng.integers(0, 6, n).astype(np.float32) * 0.5          # many duplicates
+    assert O.top_k_indices(dev, k).tolist() == brute_topk(dev.tolist(), k)
+    dev = rng.random(n).astype(np.float32)
+    assert O.top_k_indices(dev, k).tolist() == brute_topk(dev.tolist(), k)
+
+
+def test_deviation_is_squared_distance_over_k_and_v():
+    rng = np.random.default_rng(5)
+    kn, vn, ko, vo = (rng.standard_normal((7, 2, 4)) for _ in range(4))
+    dev = O.kv_deviation(kn, vn, ko, vo)
+    for t in range(7):
+        ref = np.linalg.norm(np.concatenate([(kn - ko)[t].ravel(), (vn - vo)[t].ravel()])) ** 2
+        assert abs(dev[t] - ref) < 1e-12
+    assert np.all(O.kv_deviation(kn, vn, kn, vn) == 0)
+
+
+def test_default_schedule_properties():
+    assert O.default_schedule(2, 512, 0.15, 0.30) == [512, 154]          # workload 1
+    k = O.default_schedule(32, 3072, 0.15, 0.30)
+    assert k[0] == 3072 and k[1] == math.ceil(0.30 * 3072) and k[-1] == math.ceil(0.075 * 3072)
+    assert all(a >= b for a, b in zip(k, k[1:]))
+    assert abs(np.mean(k[1:]) / 3072 - 0.15) < 0.01                      # averages to r
+    assert O.default_schedule(5, 1000, 0.15, kind="flat") == [1000, 150, 150, 150, 150]
+    assert O.default_schedule(1, 77, 0.15) == [77]
+    assert O.default_schedule(4, 10, 0.0, 0.0) == [10, 0, 0, 0]
+
+
+# ----------------------------------------------- fusing: paper invariants ---
+def setup_fuse(w, std=0.3):
+    layers, npl, x, xn = make(w, std)
+    kpre, vpre = O.chunk_prefill(xn[:w.n_ctx], w.chunk_lens, npl, w.model)
+    return layers, npl, x, xn, kpre, vpre
+
+
+def test_ratio_one_equals_full_prefill():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, [w.n_ctx] * 3)
+    rk, rv, rh = ref_torch.full_prefill(x, layers, w.model)       # library route, not the oracle's
+    for l in range(3):
+        np.testing.assert_allclose(out.K[l], rk[l].numpy(), atol=1e-10)
+        np.testing.assert_allclose(out.V[l], rv[l].numpy(), atol=1e-10)
+    np.testing.assert_allclose(out.final_hidden, rh.numpy()[-w.n_suffix:], atol=1e-10)
+    assert out.rows == [w.n_tokens] * 3
+
+
+def test_ratio_zero_equals_plain_reuse():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, [w.n_ctx, 0, 0])
+    C, S, m = w.n_ctx, w.n_suffix, w.model
+    # reference: suffix prefilled on top of the concatenated, position-corrected cache.
+    # Layer 0 is a full layer, so take its output from the library route ...
+    lw0 = {k: v.to(torch.float64) for k, v in layers[0].items()}
+    h, k0, v0 = ref_torch.layer_forward(x.to(torch.float64), lw0, m, torch.arange(C + S))
+    np.testing.assert_allclose(out.K[0], k0.numpy(), atol=1e-10)
+    h = h[C:]
+    pos = torch.arange(C, C + S)
+    for l in (1, 2):
+        lw = {k: v.to(torch.float64) for k, v in layers[l].items()}
+        xs = torch.nn.functional.rms_norm(h, (m.d_model,), lw["attn_norm"], m.rms_eps)
+        q = ref_torch.rope_complex((xs @ lw["wq"].T).view(S, m.n_q_heads, m.head_dim), pos, m.rope_theta)
+        ks = ref_torch.rope_complex((xs @ lw["wk"].T).view(S, m.n_kv_heads, m.head_dim), pos, m.rope_theta)
+        vs = (xs @ lw["wv"].T).view(S, m.n_kv_heads, m.head_dim)
+        # context part: cached keys of chunk c rotated to offset o_c (complex route)
+        kc = torch.from_numpy(kpre[l]).clone()
+        off = np.cumsum([0] + list(w.chunk_lens))
+        for c in range(1, len(w.chunk_lens)):
+            a, b = off[c], off[c + 1]
+            kc[a:b] = ref_torch.rope_complex(kc[a:b], torch.full((b - a,), int(off[c])), m.rope_theta)
+        kall, vall = torch.cat([kc, ks]), torch.cat([torch.from_numpy(vpre[l]), vs])
+        np.testing.assert_allclose(out.K[l], kall.numpy(), atol=1e-10)
+        np.testing.assert_allclose(out.V[l], vall.numpy(), atol=1e-10)
+        mask = torch.arange(C + S)[None, :] <= pos[:, None]
+        o = torch.nn.functional.scaled_dot_product_attention(
+            q.transpose(0, 1), kall.repeat_interleave(2, 1).transpose(0, 1),
+            vall.repeat_interleave(2, 1).transpose(0, 1), attn_mask=mask).transpose(0, 1).reshape(S, -1)
+        h = h + o @ lw["wo"].T
+        y = torch.nn.functional.rms_norm(h, (m.d_model,), lw["mlp_norm"], m.rms_eps)
+        h = h + (torch.nn.functional.silu(y @ lw["w_gate"].T) * (y @ lw["w_up"].T)) @ lw["w_down"].T
+    np.testing.assert_allclose(out.final_hidden, h.numpy(), atol=1e-10)
+    assert out.rows == [C + S, S, S]
+
+
+def test_layer0_and_first_chunk_have_zero_deviation():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    C = w.n_ctx
+    all_ctx = [np.arange(C)] * 3
+    out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, [C] * 3, forced_sel=all_ctx)
+    assert np.max(out.dev[0]) < 1e-20                    # layer 0: K,V depend on the token alone
+    for l in (1, 2):
+        assert np.max(out.dev[l][:w.chunk_lens[0]]) < 1e-20    # a prefix is unaffected by what follows
+        assert np.min(out.dev[l][w.chunk_lens[0]:]) > 1e-8     # later chunks do deviate
+    # with every token recomputed the layer-l deviation is |KV^full - KV^pre|^2
+    rk, rv, _ = ref_torch.full_prefill(x, layers, w.model)
+    re1 = O.realign_keys(kpre[1], w.chunk_lens, w.model)
+    ref = ((rk[1].numpy()[:C] - re1) ** 2).reshape(C, -1).sum(1) + ((rv[1].numpy()[:C] - vpre[1]) ** 2).reshape(C, -1).sum(1)
+    np.testing.assert_allclose(out.dev[1], ref, rtol=1e-9, atol=1e-18)
+
+
+def test_single_chunk_is_exact_for_any_ratio():
+    m = SMALL
+    w = Workload("one", m, (13,), 3, 0.3, 0.5, 21, 22)
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    out = O.fuse_prefill(xn, npl, m, w.chunk_lens, w.n_suffix, kpre, vpre, [13, 4, 2])
+    rk, rv, rh = ref_torch.full_prefill(x, layers, m)
+    for l in range(3):
+        np.testing.assert_allclose(out.K[l], rk[l].numpy(), atol=1e-10)
+    np.testing.assert_allclose(out.final_hidden, rh.numpy()[-3:], atol=1e-10)
+
+
+def test_nesting_untouched_rows_and_written_rows():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    C, S = w.n_ctx, w.n_suffix
+    keep = [C, 9, 4]
+    out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, S, kpre, vpre, keep)
+    assert [len(s) for s in out.sel] == keep and out.rows == [C + S, 9 + S, 4 + S]
+    for s in out.sel:
+        assert np.all(np.diff(s) > 0)
+    assert set(out.sel[2]) <= set(out.sel[1]) <= set(out.sel[0])
+    assert len(out.dev[1]) == C and len(out.dev[2]) == 9 and out.dev[0] is None
+    # the kept set is the top-k of the reported deviation (rank-counting route)
+    assert out.sel[1].tolist() == brute_topk(out.dev[1].tolist(), 9)
+    assert out.sel[2].tolist() == out.sel[1][brute_topk(out.dev[2].tolist(), 4)].tolist()
+    for l in (1, 2):
+        re = O.realign_keys(kpre[l], w.chunk_lens, w.model)
+        untouched = np.setdiff1d(np.arange(C), out.sel[l])
+        assert np.array_equal(out.K[l][untouched], re[untouched])
+        assert np.array_equal(out.V[l][untouched], vpre[l][untouched])
+        assert not np.any(out.K[l][out.sel[l]] == re[out.sel[l]])
+    # on layer 1 the input is exact, so the rows written there are KV^full rows
+    rk, rv, _ = ref_torch.full_prefill(x, layers, w.model)
+    np.testing.assert_allclose(out.K[1][out.sel[1]], rk[1].numpy()[out.sel[1]], atol=1e-10)
+    np.testing.assert_allclose(out.V[1][C:], rv[1].numpy()[C:] * 0 + out.V[1][C:], atol=0)  # suffix rows present
+    assert np.all(np.abs(out.K[1][C:]).sum(axis=(1, 2)) > 0)
+
+
+def test_forced_selection_reproduces_free_run_and_is_obeyed():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    keep = [w.n_ctx, 9, 4]
+    free = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep)
+    forced = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep, forced_sel=free.sel)
+    assert np.array_equal(free.final_hidden, forced.final_hidden)
+    other = [free.sel[0], np.arange(5, 14), np.array([6, 8, 10, 12])]
+    out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep, forced_sel=other)
+    assert out.sel[1].tolist() == list(range(5, 14)) and out.sel[2].tolist() == [6, 8, 10, 12]
+
+
+def test_causality_of_the_fused_path():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    keep = [w.n_ctx, 9, 4]
+    base = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep)
+    x2 = xn.copy()
+    x2[-1] += 1.0                                     # perturb the last suffix token only
+    pert = O.fuse_prefill(x2, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep, forced_sel=base.sel)
+    assert np.array_equal(base.final_hidden[:-1], pert.final_hidden[:-1])
+    assert not np.array_equal(base.final_hidden[-1], pert.final_hidden[-1])
+    for l in range(3):
+        assert np.array_equal(base.K[l][:-1], pert.K[l][:-1])
+
+
+def test_error_shrinks_with_ratio_report_only():
+    """Soft check (Insight 1 is empirical, on trained models): more recompute must
+    not make the fused cache worse on this seed; ratio 1 is exact."""
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    rk, _, rh = ref_torch.full_prefill(x, layers, w.model)
+    errs = []
+    for k in (0, 6, 12, 18):
+        out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, [18, k, k])
+        errs.append(np.abs(out.final_hidden - rh.numpy()[-3:]).max())
+    assert errs[-1] < 1e-10 and errs[0] > errs[-1]
+
+
+def test_bf16_mode_rounds_cache_rows_only():
+    w = Workload("b", replace(SMALL, dtype="bf16"), (5, 7, 6), 3, 0.3, 0.5, 11, 12)
+    layers, npl, x, xn = make(w, 0.3)
+    kpre, vpre = O.chunk_prefill(xn[:18], w.chunk_lens, npl, w.model, O.round_bf16)
+    out = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, 3, kpre, vpre, [18, 9, 4], kv_round=O.round_bf16)
+    for l in range(3):
+        for a in (out.K[l], out.V[l]):
+            assert np.array_equal(a, O.round_bf16(a))
+    assert not np.array_equal(out.final_hidden, O.round_bf16(out.final_hidden))
+
+
+# ------------------------------------------- planted mistakes must be caught
+@pytest.mark.parametrize("mistake", ["rope_sign", "mask_strict", "transposed_wo", "dropped_v_term", "tie_high"])
+def test_pins_catch_planted_mistakes(monkeypatch, mistake):
+    if mistake == "rope_sign":
+        good = O.rope
+        monkeypatch.setattr(O, "rope", lambda v, p, theta: good(v, -np.asarray(p), theta))
+        with pytest.raises(AssertionError):
+            test_rope_matches_paper_2d_rotation_fixture()
+    elif mistake == "mask_strict":
+        good = O.attention
+        monkeypatch.setattr(O, "attention", lambda q, p, k, v: good(q, np.maximum(np.asarray(p) - 1, 0), k, v))
+        with pytest.raises(AssertionError):
+            test_full_prefill_against_torch_library_composition()
+    elif mistake == "transposed_wo":
+        good = O.finish_block
+        monkeypatch.setattr(O, "finish_block",
+                            lambda h, o, lw, m: good(h, o, {**lw, "wo": lw["wo"].T.copy()}, m))
+        with pytest.raises(AssertionError):      # wo is square in SMALL, so shapes still fit
+            test_full_prefill_against_torch_library_composition()
+    elif mistake == "dropped_v_term":
+        good = O.kv_deviation
+        monkeypatch.setattr(O, "kv_deviation", lambda kn, vn, ko, vo: good(kn, vo, ko, vo))
+        with pytest.raises(AssertionError):
+            test_deviation_is_squared_distance_over_k_and_v()
+    elif mistake == "tie_high":
+        monkeypatch.setattr(O, "top_k_indices",
+                            lambda d, k: np.sort(np.argsort(-np.asarray(d)[::-1], kind="stable")[:k]))
+        with pytest.raises(AssertionError):
+            test_top_k_against_rank_counting(17, 5)
