@@ -1,0 +1,169 @@
+/*
+ * cacheblend.h -- C ABI of the MI355X (gfx950) CacheBlend KV-cache fusor.
+ *
+ * The library fuses N independently pre-computed per-chunk KV caches into the KV
+ * cache of the concatenated input (paper Sec. 4): the cached keys are first moved
+ * to their positions in the concatenation (Sec. 4.3 footnote, Appendix A), then,
+ * layer by layer, only a small and shrinking set of high-KV-deviation (HKVD)
+ * tokens is recomputed (Sec. 4.2, 4.3) while every other token's K/V is reused.
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says HOST.
+ *   - All buffers are owned by the caller.  The library allocates only the
+ *     cb_ctx (a host struct plus one device table of rotary cos/sin values) in
+ *     cb_create and releases it in cb_destroy.
+ *   - Storage type T = cb_model_desc.dtype (float or bfloat16) for weights, the
+ *     layer-0 input x, and the K/V caches.  The residual stream that crosses the
+ *     per-layer boundary (h_in / h_out / final_hidden) is always float.
+ *   - Weight matrices are row-major [out_features, in_features] (y = x W^T).
+ *   - A layer's K cache and V cache are separate arrays [n_tokens, n_kv_heads,
+ *     head_dim] of T, token-major; row p holds the token at global position p.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and return without synchronising the device.  Results are
+ *     valid once the caller has synchronised the stream.
+ *   - Return value: CB_OK (0) or a negative cb_status.  Arguments are validated
+ *     before the first launch, so a failing call leaves every buffer untouched
+ *     (CB_EHIP, a launch failure reported by the runtime, is the exception).
+ *   - One cb_ctx serves one stream at a time; calls on the same ctx must not
+ *     overlap.  Different ctx objects are independent.
+ */
+#ifndef CACHEBLEND_H
+#define CACHEBLEND_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CB_OK = 0,
+  CB_EINVAL = -1,       /* bad shape / argument */
+  CB_ENULL = -2,        /* required pointer is NULL */
+  CB_EWORKSPACE = -3,   /* workspace too small */
+  CB_EUNSUPPORTED = -4, /* geometry the kernels do not cover */
+  CB_EHIP = -5,         /* HIP runtime reported an error */
+  CB_ENOMEM = -6        /* allocation of the ctx failed */
+} cb_status;
+
+typedef enum { CB_F32 = 0, CB_BF16 = 1 } cb_dtype;
+
+/* Decoder geometry (RMSNorm, grouped-query attention, rotary embedding on
+ * adjacent channel pairs as in Appendix A, SwiGLU MLP, no biases). */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
+  float rms_eps, rope_theta;
+  int32_t dtype; /* cb_dtype */
+} cb_model_desc;
+
+/* One layer's weights (all of storage type T). */
+typedef struct {
+  const void *attn_norm;      /* [d_model] */
+  const void *wq, *wk, *wv;   /* [Hq*dh, d], [Hkv*dh, d], [Hkv*dh, d] */
+  const void *wo;             /* [d, Hq*dh] */
+  const void *mlp_norm;       /* [d_model] */
+  const void *w_gate, *w_up;  /* [d_ff, d] */
+  const void *w_down;         /* [d, d_ff] */
+} cb_layer_weights;
+
+typedef struct cb_ctx cb_ctx;
+
+/* Creates a context for one model geometry; positions 0 .. max_tokens-1 are
+ * covered by the rotary table.  desc and out are HOST pointers. */
+int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out);
+void cb_destroy(cb_ctx *ctx);
+const char *cb_strerror(int status);
+
+/* Bytes of workspace cb_fuse_layer needs for calls with n_rows <= max_rows. */
+size_t cb_layer_workspace_bytes(const cb_ctx *ctx, int32_t max_rows);
+/* Bytes of workspace cb_fuse_prefill needs for n_tokens = context + suffix. */
+size_t cb_prefill_workspace_bytes(const cb_ctx *ctx, int32_t n_tokens);
+
+/* Gradual-filtering schedule (Sec. 4.3): keep_counts[0] = n_ctx; for l >= 1 the
+ * kept fraction falls from r1 on layer 1 to (3r - r1)/2 on the last layer along
+ * (1-t)^2, so it averages r; counts are ceil(fraction * n_ctx), non-increasing.
+ * r1 <= 0 selects r1 = 2r; flat != 0 gives ceil(r * n_ctx) on every layer >= 1.
+ * keep_counts: HOST int32[n_layers]. */
+int cb_default_schedule(int32_t n_layers, int32_t n_ctx, double r, double r1, int32_t flat,
+                        int32_t *keep_counts);
+
+/* Positional recovery of cached keys (Sec. 4.3 footnote; Appendix A).
+ * Chunk c was prefilled at positions 0.., so its cached keys carry R(t); this
+ * multiplies rows [o_c, o_{c+1}) of every given layer's K cache by R(o_c), in
+ * place.  Chunk 0 and all V caches are not touched.
+ *   k_cache_layers : HOST array [n_layers] of device base pointers (T [*, Hkv, dh])
+ *   layer_begin/end: half-open layer range to process
+ *   chunk_offsets  : HOST int32[n_chunks + 1], o_0 = 0 < o_1 < ... <= max_tokens */
+int cb_realign_rope(cb_ctx *ctx, void *const *k_cache_layers, int32_t layer_begin,
+                    int32_t layer_end, const int32_t *chunk_offsets, int32_t n_chunks,
+                    void *stream);
+
+/* One layer of selective recompute (Sec. 4.2 workflow; Sec. 6 prefill_layer with
+ * its check_flag / HKVD_indices).
+ *   h_in    : float [n_rows, d]   this layer's input for the rows that survived
+ *   row_pos : int32 [n_rows]      their global positions, strictly ascending;
+ *                                 the LAST n_suffix rows are the suffix (never
+ *                                 candidates, always kept)
+ *   k_cache, v_cache : T [n_tokens_total, Hkv, dh]; in: re-aligned pre-computed
+ *                      rows (rows of the suffix may hold anything); out: rows of
+ *                      the kept tokens overwritten with their new K/V, all other
+ *                      rows unchanged
+ *   k_keep  : number of context rows to keep, 0 <= k_keep <= n_rows - n_suffix.
+ *             k_keep == n_rows - n_suffix without forced_sel means "no check":
+ *             the deviation and top-k steps are skipped.
+ *   forced_sel : NULL, or int32 [k_keep] strictly ascending positions taken from
+ *             row_pos's context part, kept instead of the top-k (the deviation is
+ *             still computed).  Positions that are not candidates give undefined
+ *             selections but no out-of-bounds access.
+ *   h_out   : float [k_keep + n_suffix, d]   next layer's input
+ *   pos_out : int32 [k_keep + n_suffix]      positions of those rows, ascending
+ *   dev_out : NULL, or float [n_rows - n_suffix]: squared L2 deviation of each
+ *             candidate's new K/V from its cached K/V, in row order (written only
+ *             when the check runs)
+ * Kept = the k_keep candidates with the largest deviation, equal values going
+ * to the lower position.  h_out/pos_out must not alias h_in/row_pos. */
+int cb_fuse_layer(cb_ctx *ctx, int32_t layer, const cb_layer_weights *weights /*HOST*/,
+                  const float *h_in, const int32_t *row_pos, int32_t n_rows, int32_t n_suffix,
+                  void *k_cache, void *v_cache, int32_t n_tokens_total, int32_t k_keep,
+                  const int32_t *forced_sel, float *h_out, int32_t *pos_out, float *dev_out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* Whole fusing pass (Sec. 4; Sec. 5.1 "fusor"): cb_realign_rope on every layer,
+ * then cb_fuse_layer for layers 0 .. L-1, each layer's survivors feeding the next.
+ *   layers        : HOST array [L] of cb_layer_weights
+ *   x             : T [n_ctx + n_suffix, d] layer-0 input, context tokens chunk
+ *                   after chunk, then the suffix
+ *   chunk_lens    : HOST int32[n_chunks], each >= 1
+ *   k_cache_layers, v_cache_layers : HOST arrays [L] of device pointers to
+ *                   T [n_ctx + n_suffix, Hkv, dh]; rows [0, n_ctx) hold the chunks'
+ *                   pre-computed K/V as cached at positions 0.. (NOT re-aligned)
+ *   keep_counts   : HOST int32[L], keep_counts[0] == n_ctx, non-increasing
+ *   forced_sel    : NULL, or HOST array [L] of (NULL | device int32[keep_counts[l]])
+ *   final_hidden  : float [n_suffix, d] residual stream after the last layer
+ *   sel_dump      : NULL, or HOST array [L] of (NULL | device int32[keep_counts[l]])
+ *                   receiving the kept context positions of layer l
+ *   dev_dump      : NULL, or HOST array [L] of (NULL | device float[candidates of
+ *                   layer l]) receiving that layer's deviation vector */
+int cb_fuse_prefill(cb_ctx *ctx, const cb_layer_weights *layers, const void *x,
+                    const int32_t *chunk_lens, int32_t n_chunks, int32_t n_suffix,
+                    void *const *k_cache_layers, void *const *v_cache_layers,
+                    const int32_t *keep_counts, const int32_t *const *forced_sel,
+                    float *final_hidden, int32_t *const *sel_dump, float *const *dev_dump,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/* Per-kernel-class timing for benchmarks.  Classes: */
+enum { CB_PROF_GEMM = 0, CB_PROF_ATTN = 1, CB_PROF_REALIGN = 2, CB_PROF_DEV = 3,
+       CB_PROF_TOPK = 4, CB_PROF_NORM = 5, CB_PROF_OTHER = 6, CB_PROF_NCLASS = 7 };
+/* enable != 0: every later launch on ctx is bracketed by a pair of HIP events on
+ * its stream (this slows the pass a little; do not time whole calls meanwhile). */
+int cb_profile_enable(cb_ctx *ctx, int32_t enable);
+/* Synchronises the events recorded since the last read, adds up milliseconds,
+ * launch counts, algorithmic flops and algorithmic bytes per class into HOST
+ * arrays of CB_PROF_NCLASS entries each, and resets the record. */
+int cb_profile_read(cb_ctx *ctx, double *ms, int64_t *launches, double *flops, double *bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CACHEBLEND_H */

@@ -1,0 +1,483 @@
+// C ABI and host orchestration of the CacheBlend fusor (see include/cacheblend.h).
+// Sequencing follows the paper's per-layer workflow (Sec. 4.2) with the check step
+// of Sec. 6 placed right after the K/V projection: project K/V of the rows that
+// reached the layer, measure their deviation from the cached K/V, keep the top-k,
+// write only the kept rows into the cache, and run Q / attention / MLP on the kept
+// rows alone.  Nothing here synchronises the device; row counts are known on the
+// host because the keep counts are inputs.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/cacheblend.h"
+#include "common.h"
+#include "kernels.h"
+
+using namespace cb;
+
+struct ProfRec {
+  int cls;
+  hipEvent_t start, stop;
+  double flops, bytes;
+};
+
+struct cb_ctx {
+  cb_model_desc m;
+  int max_tokens;
+  int device;
+  float2 *rope_tab;  // device [max_tokens][head_dim/2]
+  bool profiling;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> free_events;
+};
+
+namespace {
+
+size_t esize(const cb_ctx *c) { return c->m.dtype == CB_BF16 ? 2 : 4; }
+
+hipEvent_t take_event(cb_ctx *c) {
+  if (!c->free_events.empty()) {
+    hipEvent_t e = c->free_events.back();
+    c->free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+// brackets one launch (or launch group) with events when profiling is on
+struct ProfScope {
+  cb_ctx *c;
+  hipStream_t s;
+  ProfRec r;
+  bool on;
+  ProfScope(cb_ctx *ctx, hipStream_t st, int cls, double flops, double bytes) : c(ctx), s(st) {
+    on = ctx->profiling;
+    if (!on) return;
+    r.cls = cls; r.flops = flops; r.bytes = bytes;
+    r.start = take_event(c);
+    r.stop = take_event(c);
+    (void)hipEventRecord(r.start, s);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(r.stop, s);
+    c->recs.push_back(r);
+  }
+};
+
+struct LayerWs {
+  void *xn, *kvnew, *qbuf, *obuf, *act;
+  float *hmid, *partial, *dev;
+  int32_t *sel_rows;
+  size_t partial_floats;
+  size_t bytes;
+};
+
+size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
+  const cb_model_desc &m = c->m;
+  const int bm = m.dtype == CB_BF16 ? 128 : 64;
+  size_t need = 0;
+  const int shapes[2] = {m.n_q_heads * m.head_dim, m.d_ff};
+  for (int M = 1; M <= max_rows; M = (M == max_rows) ? max_rows + 1 : std::min(max_rows, (M / bm + 1) * bm)) {
+    for (int K : shapes) {
+      int s = gemm_splits(m.dtype, M, m.d_model, K);
+      if (s > 1) need = std::max(need, (size_t)s * M * m.d_model);
+    }
+  }
+  return need;
+}
+
+// carve the per-layer workspace out of [base, base + avail); base may be NULL to size only
+LayerWs carve_layer(const cb_ctx *c, char *base, int R) {
+  const cb_model_desc &m = c->m;
+  const size_t es = esize(c);
+  const size_t q_dim = (size_t)m.n_q_heads * m.head_dim, kv_dim = (size_t)m.n_kv_heads * m.head_dim;
+  LayerWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char *p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return (void *)p;
+  };
+  w.xn = take((size_t)R * m.d_model * es);
+  w.kvnew = take((size_t)R * 2 * kv_dim * es);
+  w.qbuf = take((size_t)R * q_dim * es);
+  w.obuf = take((size_t)R * q_dim * es);
+  w.act = take((size_t)R * m.d_ff * es);
+  w.hmid = (float *)take((size_t)R * m.d_model * 4);
+  w.partial_floats = partial_floats_needed(c, R);
+  w.partial = (float *)take(w.partial_floats * 4);
+  w.dev = (float *)take((size_t)R * 4);
+  w.sel_rows = (int32_t *)take((size_t)R * 4);
+  w.bytes = off;
+  return w;
+}
+
+__global__ void iota_kernel(int32_t *p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = i;
+}
+
+#define CB_HIP(expr)                     \
+  do {                                   \
+    hipError_t e_ = (expr);              \
+    if (e_ != hipSuccess) return CB_EHIP; \
+  } while (0)
+
+int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int n_rows, int n_suffix,
+                     int n_tokens_total, int k_keep) {
+  if (!c || !w) return CB_ENULL;
+  if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up ||
+      !w->w_down)
+    return CB_ENULL;
+  if (layer < 0 || layer >= c->m.n_layers) return CB_EINVAL;
+  if (n_rows < 0 || n_suffix < 0 || n_suffix > n_rows) return CB_EINVAL;
+  if (k_keep < 0 || k_keep > n_rows - n_suffix) return CB_EINVAL;
+  if (n_tokens_total < 1 || n_tokens_total > c->max_tokens || n_rows > n_tokens_total) return CB_EINVAL;
+  return CB_OK;
+}
+
+// the layer body; arguments already validated
+int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, const int32_t *row_pos,
+                    int n, int S, void *kc, void *vc, int k, const int32_t *forced, float *h_out,
+                    int32_t *pos_out, float *dev_out, const LayerWs &ws, hipStream_t s) {
+  const cb_model_desc &m = c->m;
+  const int dt = m.dtype;
+  const size_t es = esize(c);
+  const int d = m.d_model, q_dim = m.n_q_heads * m.head_dim, kv_dim = m.n_kv_heads * m.head_dim;
+  const int F = m.d_ff;
+  const int n_cand = n - S, rows = k + S;
+  const bool check = (k < n_cand) || forced != nullptr;
+  if (n == 0) return CB_OK;
+
+  {
+    ProfScope ps(c, s, CB_PROF_NORM, 0, (double)n * d * (4 + es));
+    CB_HIP(launch_rmsnorm(dt, h_in, w->attn_norm, ws.xn, n, d, m.rms_eps, s));
+  }
+  GemmArgs g = {};
+  g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim;
+  const int32_t *sel_rows = nullptr;
+  if (check) {
+    // K/V of every row that reached this layer (Sec. 6: "newly computed KV")
+    g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = 2;
+    g.seg[0] = {w->wk, kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1};
+    g.seg[1] = {w->wv, kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0};
+    g.row_pos = row_pos;
+    {
+      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * 2 * kv_dim,
+                   ((double)2 * kv_dim * d + (double)n * d + (double)n * 2 * kv_dim) * es);
+      CB_HIP(launch_gemm(g, s));
+    }
+    float *dev = dev_out ? dev_out : ws.dev;
+    {
+      ProfScope ps(c, s, CB_PROF_DEV, 4.0 * n_cand * 2 * kv_dim, (double)n_cand * (4.0 * kv_dim * es + 4));
+      CB_HIP(launch_deviation(dt, ws.kvnew, row_pos, n_cand, kc, vc, kv_dim, dev, s));
+    }
+    {
+      ProfScope ps(c, s, CB_PROF_TOPK, 0, (double)n_cand * 4 + (double)rows * 8);
+      if (forced) CB_HIP(launch_forced_map(forced, k, row_pos, n_cand, S, ws.sel_rows, pos_out, s));
+      else CB_HIP(launch_topk(dev, n_cand, k, S, row_pos, ws.sel_rows, pos_out, s));
+    }
+    if (rows == 0) return CB_OK;
+    sel_rows = ws.sel_rows;
+    {
+      // only the kept tokens' KV is updated (Sec. 6)
+      ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)rows * 4 * kv_dim * es);
+      CB_HIP(launch_scatter_kv(dt, ws.kvnew, sel_rows, pos_out, rows, kc, vc, kv_dim, s));
+    }
+    g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
+    g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
+    g.row_pos = pos_out;
+    {
+      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * q_dim,
+                   ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es);
+      CB_HIP(launch_gemm(g, s));
+    }
+  } else {
+    // every row is kept: one fused Q|K|V projection, K and V written straight into the cache
+    {
+      ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)n * 8);
+      CB_HIP(hipMemcpyAsync(pos_out, row_pos, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
+    }
+    g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = 3;
+    g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
+    g.seg[1] = {w->wk, kv_dim, kc, kv_dim, row_pos, 1};
+    g.seg[2] = {w->wv, kv_dim, vc, kv_dim, row_pos, 0};
+    g.row_pos = row_pos;
+    {
+      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * (q_dim + 2 * kv_dim),
+                   ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es);
+      CB_HIP(launch_gemm(g, s));
+    }
+  }
+  {
+    ProfScope ps(c, s, CB_PROF_ATTN, 0, 0);
+    CB_HIP(launch_attention(dt, ws.qbuf, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads, m.n_kv_heads,
+                            m.head_dim, s));
+  }
+  // h = H + o Wo^T
+  GemmArgs f = {};
+  f.dtype = dt; f.a = ws.obuf; f.lda = q_dim; f.M = rows; f.K = q_dim; f.epi = EPI_F32; f.n_seg = 1;
+  f.seg[0].w = w->wo; f.seg[0].n = d;
+  f.out_f32 = ws.hmid; f.resid = h_in; f.resid_rows = sel_rows;
+  f.partial = ws.partial; f.partial_floats = ws.partial_floats;
+  {
+    ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * q_dim * d,
+                 ((double)q_dim * d + (double)rows * q_dim) * es + (double)rows * d * 8);
+    CB_HIP(launch_gemm(f, s));
+  }
+  {
+    ProfScope ps(c, s, CB_PROF_NORM, 0, (double)rows * d * (4 + es));
+    CB_HIP(launch_rmsnorm(dt, ws.hmid, w->mlp_norm, ws.xn, rows, d, m.rms_eps, s));
+  }
+  GemmArgs u = {};
+  u.dtype = dt; u.a = ws.xn; u.lda = d; u.M = rows; u.K = d; u.epi = EPI_SWIGLU; u.n_seg = 2;
+  u.seg[0] = {w->w_gate, F, ws.act, F, nullptr, 0};
+  u.seg[1] = {w->w_up, F, nullptr, 0, nullptr, 0};
+  {
+    ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * 2 * F,
+                 ((double)2 * F * d + (double)rows * d + (double)rows * F) * es);
+    CB_HIP(launch_gemm(u, s));
+  }
+  f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = w->w_down;
+  f.out_f32 = h_out; f.resid = ws.hmid; f.resid_rows = nullptr;
+  {
+    ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * F * d,
+                 ((double)F * d + (double)rows * F) * es + (double)rows * d * 8);
+    CB_HIP(launch_gemm(f, s));
+  }
+  return CB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *cb_strerror(int status) {
+  switch (status) {
+    case CB_OK: return "ok";
+    case CB_EINVAL: return "invalid argument";
+    case CB_ENULL: return "null pointer";
+    case CB_EWORKSPACE: return "workspace too small";
+    case CB_EUNSUPPORTED: return "unsupported model geometry";
+    case CB_EHIP: return "HIP runtime error";
+    case CB_ENOMEM: return "out of memory";
+    default: return "unknown status";
+  }
+}
+
+int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out) {
+  if (!desc || !out) return CB_ENULL;
+  *out = nullptr;
+  const cb_model_desc &m = *desc;
+  if (m.n_layers < 1 || m.d_model < 8 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.d_ff < 8 ||
+      max_tokens < 1 || max_tokens > (1 << 24) || !(m.rms_eps > 0.f) || !(m.rope_theta > 0.f))
+    return CB_EINVAL;
+  if (m.dtype != CB_F32 && m.dtype != CB_BF16) return CB_EINVAL;
+  if (m.head_dim != 64 && m.head_dim != 128) return CB_EUNSUPPORTED;
+  if (m.n_q_heads % m.n_kv_heads != 0) return CB_EUNSUPPORTED;
+  if (m.d_model % 8 != 0 || m.d_ff % 8 != 0) return CB_EUNSUPPORTED;  // 16-byte operand vectors
+  cb_ctx *c = new (std::nothrow) cb_ctx();
+  if (!c) return CB_ENOMEM;
+  c->m = m;
+  c->max_tokens = max_tokens;
+  c->profiling = false;
+  c->rope_tab = nullptr;
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CB_EHIP; }
+  // rotary table in double precision on the host: (cos, sin)(p * theta^(-2i/dh)) (Appendix A)
+  const int half = m.head_dim / 2;
+  std::vector<float2> tab((size_t)max_tokens * half);
+  std::vector<double> freq(half);
+  for (int i = 0; i < half; ++i) freq[i] = std::pow((double)m.rope_theta, -2.0 * i / m.head_dim);
+  for (int p = 0; p < max_tokens; ++p)
+    for (int i = 0; i < half; ++i) {
+      const double a = (double)p * freq[i];
+      tab[(size_t)p * half + i] = make_float2((float)std::cos(a), (float)std::sin(a));
+    }
+  if (hipMalloc(&c->rope_tab, tab.size() * sizeof(float2)) != hipSuccess) { delete c; return CB_ENOMEM; }
+  if (hipMemcpy(c->rope_tab, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(c->rope_tab);
+    delete c;
+    return CB_EHIP;
+  }
+  *out = c;
+  return CB_OK;
+}
+
+void cb_destroy(cb_ctx *c) {
+  if (!c) return;
+  for (auto &r : c->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  for (auto e : c->free_events) (void)hipEventDestroy(e);
+  if (c->rope_tab) (void)hipFree(c->rope_tab);
+  delete c;
+}
+
+size_t cb_layer_workspace_bytes(const cb_ctx *c, int32_t max_rows) {
+  if (!c || max_rows < 1) return 0;
+  return carve_layer(c, nullptr, max_rows).bytes;
+}
+
+size_t cb_prefill_workspace_bytes(const cb_ctx *c, int32_t n_tokens) {
+  if (!c || n_tokens < 1) return 0;
+  size_t h = align_up((size_t)n_tokens * c->m.d_model * 4, 256);
+  size_t p = align_up((size_t)n_tokens * 4, 256);
+  return 2 * h + 2 * p + carve_layer(c, nullptr, n_tokens).bytes;
+}
+
+int cb_default_schedule(int32_t n_layers, int32_t n_ctx, double r, double r1, int32_t flat,
+                        int32_t *keep_counts) {
+  if (!keep_counts) return CB_ENULL;
+  if (n_layers < 1 || n_ctx < 0 || !(r >= 0.0) || r > 1.0) return CB_EINVAL;
+  const double rd = r, r1d = (r1 > 0.0) ? r1 : 2.0 * rd;
+  const double r_end = (3.0 * rd - r1d) / 2.0;
+  keep_counts[0] = n_ctx;
+  for (int l = 1; l < n_layers; ++l) {
+    double rl = rd;
+    if (!flat) {
+      const double t = (double)(l - 1) / (double)std::max(1, n_layers - 2);
+      rl = r_end + (r1d - r_end) * (1.0 - t) * (1.0 - t);
+    }
+    long k = (long)std::ceil(rl * n_ctx - 1e-9);
+    if (k < 0) k = 0;
+    if (k > keep_counts[l - 1]) k = keep_counts[l - 1];
+    keep_counts[l] = (int32_t)k;
+  }
+  return CB_OK;
+}
+
+int cb_realign_rope(cb_ctx *c, void *const *k_cache_layers, int32_t layer_begin, int32_t layer_end,
+                    const int32_t *chunk_offsets, int32_t n_chunks, void *stream) {
+  if (!c || !k_cache_layers || !chunk_offsets) return CB_ENULL;
+  if (layer_begin < 0 || layer_end > c->m.n_layers || layer_begin > layer_end || n_chunks < 1)
+    return CB_EINVAL;
+  if (chunk_offsets[0] != 0) return CB_EINVAL;
+  for (int i = 0; i < n_chunks; ++i)
+    if (chunk_offsets[i + 1] <= chunk_offsets[i]) return CB_EINVAL;
+  if (chunk_offsets[n_chunks] > c->max_tokens) return CB_EINVAL;
+  for (int l = layer_begin; l < layer_end; ++l)
+    if (!k_cache_layers[l]) return CB_ENULL;
+  if (layer_begin == layer_end || n_chunks == 1) return CB_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const int kv_dim = c->m.n_kv_heads * c->m.head_dim;
+  const double moved = 2.0 * (layer_end - layer_begin) *
+                       (double)(chunk_offsets[n_chunks] - chunk_offsets[1]) * kv_dim * esize(c);
+  ProfScope ps(c, s, CB_PROF_REALIGN, 0, moved);
+  CB_HIP(launch_realign(c->m.dtype, k_cache_layers + layer_begin, layer_end - layer_begin, chunk_offsets,
+                        n_chunks, kv_dim, c->m.head_dim, c->rope_tab, s));
+  return CB_OK;
+}
+
+int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const float *h_in,
+                  const int32_t *row_pos, int32_t n_rows, int32_t n_suffix, void *k_cache, void *v_cache,
+                  int32_t n_tokens_total, int32_t k_keep, const int32_t *forced_sel, float *h_out,
+                  int32_t *pos_out, float *dev_out, void *workspace, size_t workspace_bytes,
+                  void *stream) {
+  int st = check_layer_args(c, layer, w, n_rows, n_suffix, n_tokens_total, k_keep);
+  if (st != CB_OK) return st;
+  if (!h_in || !row_pos || !k_cache || !v_cache || !h_out || !pos_out || !workspace) return CB_ENULL;
+  if (h_out == h_in || pos_out == row_pos) return CB_EINVAL;
+  if (n_rows == 0) return CB_OK;
+  LayerWs ws = carve_layer(c, (char *)workspace, n_rows);
+  if (ws.bytes > workspace_bytes) return CB_EWORKSPACE;
+  return fuse_layer_impl(c, w, h_in, row_pos, n_rows, n_suffix, k_cache, v_cache, k_keep, forced_sel,
+                         h_out, pos_out, dev_out, ws, (hipStream_t)stream);
+}
+
+int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, const int32_t *chunk_lens,
+                    int32_t n_chunks, int32_t n_suffix, void *const *k_cache_layers,
+                    void *const *v_cache_layers, const int32_t *keep_counts,
+                    const int32_t *const *forced_sel, float *final_hidden, int32_t *const *sel_dump,
+                    float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !layers || !x || !chunk_lens || !k_cache_layers || !v_cache_layers || !keep_counts ||
+      !workspace)
+    return CB_ENULL;
+  if (n_chunks < 1 || n_suffix < 0) return CB_EINVAL;
+  if (n_suffix > 0 && !final_hidden) return CB_ENULL;
+  const int L = c->m.n_layers, d = c->m.d_model;
+  std::vector<int32_t> off(n_chunks + 1, 0);
+  for (int i = 0; i < n_chunks; ++i) {
+    if (chunk_lens[i] < 1) return CB_EINVAL;
+    if ((long)off[i] + chunk_lens[i] > c->max_tokens) return CB_EINVAL;
+    off[i + 1] = off[i] + chunk_lens[i];
+  }
+  const int C = off[n_chunks];
+  if ((long)C + n_suffix > c->max_tokens) return CB_EINVAL;
+  const int T = C + n_suffix;
+  if (keep_counts[0] != C) return CB_EINVAL;
+  for (int l = 1; l < L; ++l)
+    if (keep_counts[l] < 0 || keep_counts[l] > keep_counts[l - 1]) return CB_EINVAL;
+  for (int l = 0; l < L; ++l) {
+    if (!k_cache_layers[l] || !v_cache_layers[l]) return CB_ENULL;
+    int st = check_layer_args(c, l, &layers[l], T, n_suffix, T, 0);
+    if (st != CB_OK) return st;
+  }
+  if (cb_prefill_workspace_bytes(c, T) > workspace_bytes) return CB_EWORKSPACE;
+
+  hipStream_t s = (hipStream_t)stream;
+  char *base = (char *)workspace;
+  const size_t hb = align_up((size_t)T * d * 4, 256), pb = align_up((size_t)T * 4, 256);
+  float *h_cur = (float *)base, *h_nxt = (float *)(base + hb);
+  int32_t *p_cur = (int32_t *)(base + 2 * hb), *p_nxt = (int32_t *)(base + 2 * hb + pb);
+  LayerWs ws = carve_layer(c, base + 2 * hb + 2 * pb, T);
+
+  {
+    ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)T * d * (4 + esize(c)));
+    CB_HIP(launch_to_f32(c->m.dtype, x, h_cur, (size_t)T * d, s));
+    hipLaunchKernelGGL(iota_kernel, dim3((T + 255) / 256), dim3(256), 0, s, p_cur, T);
+    CB_HIP(hipGetLastError());
+  }
+  int st = cb_realign_rope(c, k_cache_layers, 0, L, off.data(), n_chunks, stream);
+  if (st != CB_OK) return st;
+
+  int n = T;
+  for (int l = 0; l < L; ++l) {
+    const int k = keep_counts[l];
+    const int32_t *forced = forced_sel ? forced_sel[l] : nullptr;
+    float *dev_out = dev_dump ? dev_dump[l] : nullptr;
+    st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, n, n_suffix, k_cache_layers[l], v_cache_layers[l],
+                         k, forced, h_nxt, p_nxt, dev_out, ws, s);
+    if (st != CB_OK) return st;
+    if (sel_dump && sel_dump[l] && k > 0)
+      CB_HIP(hipMemcpyAsync(sel_dump[l], p_nxt, (size_t)k * 4, hipMemcpyDeviceToDevice, s));
+    std::swap(h_cur, h_nxt);
+    std::swap(p_cur, p_nxt);
+    n = k + n_suffix;
+  }
+  if (n_suffix > 0) {
+    ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)n_suffix * d * 8);
+    CB_HIP(launch_copy_rows_f32(h_cur + (size_t)(n - n_suffix) * d, final_hidden, (size_t)n_suffix * d, s));
+  }
+  return CB_OK;
+}
+
+int cb_profile_enable(cb_ctx *c, int32_t enable) {
+  if (!c) return CB_ENULL;
+  c->profiling = enable != 0;
+  return CB_OK;
+}
+
+int cb_profile_read(cb_ctx *c, double *ms, int64_t *launches, double *flops, double *bytes) {
+  if (!c || !ms || !launches || !flops || !bytes) return CB_ENULL;
+  for (int i = 0; i < CB_PROF_NCLASS; ++i) { ms[i] = 0; launches[i] = 0; flops[i] = 0; bytes[i] = 0; }
+  if (!c->recs.empty()) CB_HIP(hipEventSynchronize(c->recs.back().stop));
+  for (auto &r : c->recs) {
+    float t = 0.f;
+    CB_HIP(hipEventElapsedTime(&t, r.start, r.stop));
+    ms[r.cls] += t;
+    launches[r.cls] += 1;
+    flops[r.cls] += r.flops;
+    bytes[r.cls] += r.bytes;
+    c->free_events.push_back(r.start);
+    c->free_events.push_back(r.stop);
+  }
+  c->recs.clear();
+  return CB_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,242 @@
+// Bandwidth-bound kernels: positional re-alignment of cached keys (paper Sec. 4.3
+// footnote / Appendix A), RMSNorm, the per-token KV deviation (Sec. 4.1, Sec. 6),
+// the scatter of recomputed K/V rows into the fused cache (Sec. 4.2) and copies.
+#include "common.h"
+#include "kernels.h"
+#include <algorithm>
+
+namespace cb {
+
+// ---------------------------------------------------------------------------
+// Re-alignment.  grid = (token tiles of the longest chunk, chunks >= 1 of this
+// batch, layers of this batch).  All lanes of a block share one chunk, so the
+// rotation (cos, sin) row of the table is the same for every token of the block.
+// Each lane moves 16-byte vectors: several independent loads are issued before
+// the first store to keep enough bytes in flight for HBM.
+// ---------------------------------------------------------------------------
+constexpr int kRealignLayers = 32;
+constexpr int kRealignChunks = 64;
+constexpr int kRealignTok = 8;
+struct RealignArgs {
+  void *layer[kRealignLayers];
+  int32_t off[kRealignChunks + 1];  // off[i]..off[i+1] = rows of the i-th chunk of the batch
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void realign_kernel(RealignArgs a, int kv_dim, int head_dim,
+                                                      const float2 *__restrict__ rope_tab) {
+  using V = Vec16<T>;
+  const int c = blockIdx.y;
+  const int begin = a.off[c], end = a.off[c + 1];
+  const int tok0 = begin + blockIdx.x * kRealignTok;
+  if (tok0 >= end) return;
+  const int ntok = min(kRealignTok, end - tok0);
+  const int vec_per_row = kv_dim / V::N;
+  const int total = ntok * vec_per_row;
+  V *base = reinterpret_cast<V *>(reinterpret_cast<T *>(a.layer[blockIdx.z]) + (size_t)tok0 * kv_dim);
+  const float2 *tab = rope_tab + (size_t)begin * (head_dim / 2);  // rotation by the offset o_c
+  constexpr int U = 4;
+  for (int i0 = threadIdx.x; i0 < total; i0 += 256 * U) {
+    V v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = i0 + u * 256;
+      if (i < total) v[u] = base[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int i = i0 + u * 256;
+      if (i < total) {
+        int e0 = (i % vec_per_row) * V::N;       // first channel of this vector in the row
+        int pair0 = (e0 % head_dim) / 2;
+        V o;
+#pragma unroll
+        for (int j = 0; j < V::N / 2; ++j) {
+          float2 cs = tab[pair0 + j];
+          float x0 = v[u].get(2 * j), x1 = v[u].get(2 * j + 1);
+          o.set(2 * j, x0 * cs.x - x1 * cs.y);
+          o.set(2 * j + 1, x0 * cs.y + x1 * cs.x);
+        }
+        base[i] = o;
+      }
+    }
+  }
+}
+
+hipError_t launch_realign(int dtype, void *const *k_layers, int n_layers, const int32_t *offs,
+                          int n_chunks, int kv_dim, int head_dim, const float2 *rope_tab,
+                          hipStream_t s) {
+  for (int l0 = 0; l0 < n_layers; l0 += kRealignLayers) {
+    int nl = std::min(kRealignLayers, n_layers - l0);
+    for (int c0 = 1; c0 < n_chunks; c0 += kRealignChunks) {
+      int nc = std::min(kRealignChunks, n_chunks - c0);
+      RealignArgs a;
+      for (int i = 0; i < kRealignLayers; ++i) a.layer[i] = k_layers[l0 + std::min(i, nl - 1)];
+      int maxlen = 0;
+      for (int i = 0; i <= kRealignChunks; ++i) a.off[i] = offs[c0 + std::min(i, nc)];
+      for (int i = 0; i < nc; ++i) maxlen = std::max(maxlen, a.off[i + 1] - a.off[i]);
+      if (maxlen <= 0) continue;
+      dim3 grid((maxlen + kRealignTok - 1) / kRealignTok, nc, nl);
+      if (dtype == 0)
+        hipLaunchKernelGGL(realign_kernel<float>, grid, dim3(256), 0, s, a, kv_dim, head_dim, rope_tab);
+      else
+        hipLaunchKernelGGL(realign_kernel<bf16>, grid, dim3(256), 0, s, a, kv_dim, head_dim, rope_tab);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+  }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void to_f32_kernel(const T *__restrict__ x, float *__restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = to_f32(x[i]);
+}
+hipError_t launch_to_f32(int dtype, const void *x, float *out, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)std::min<size_t>((n + 255) / 256, 65536);
+  if (dtype == 0)
+    hipLaunchKernelGGL(to_f32_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)x, out, n);
+  else
+    hipLaunchKernelGGL(to_f32_kernel<bf16>, dim3(blocks), dim3(256), 0, s, (const bf16 *)x, out, n);
+  return hipGetLastError();
+}
+
+__global__ void copy_f32_kernel(const float4 *__restrict__ in, float4 *__restrict__ out, size_t n4) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n4; i += stride) out[i] = in[i];
+}
+hipError_t launch_copy_rows_f32(const float *in, float *out, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t n4 = n / 4;  // callers pass multiples of 4 (d_model % 8 == 0)
+  int blocks = (int)std::min<size_t>((n4 + 255) / 256, 65536);
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, s, (const float4 *)in, (float4 *)out, n4);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// RMSNorm: one block per row; the row (float) is read twice (second read hits L2).
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h,
+                                                      const T *__restrict__ gain,
+                                                      T *__restrict__ out, int d, float eps) {
+  __shared__ float red[4];
+  const float4 *row = reinterpret_cast<const float4 *>(h + (size_t)blockIdx.x * d);
+  const int n4 = d / 4;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    float4 v = row[i];
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  T *orow = out + (size_t)blockIdx.x * d;
+  for (int i = threadIdx.x; i < n4; i += 256) {
+    float4 v = row[i];
+    orow[4 * i + 0] = from_f32<T>(v.x * inv * to_f32(gain[4 * i + 0]));
+    orow[4 * i + 1] = from_f32<T>(v.y * inv * to_f32(gain[4 * i + 1]));
+    orow[4 * i + 2] = from_f32<T>(v.z * inv * to_f32(gain[4 * i + 2]));
+    orow[4 * i + 3] = from_f32<T>(v.w * inv * to_f32(gain[4 * i + 3]));
+  }
+}
+hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int n_rows, int d,
+                          float eps, hipStream_t s) {
+  if (n_rows == 0) return hipSuccess;
+  if (dtype == 0)
+    hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n_rows), dim3(256), 0, s, h, (const float *)gain,
+                       (float *)out, d, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_kernel<bf16>, dim3(n_rows), dim3(256), 0, s, h, (const bf16 *)gain,
+                       (bf16 *)out, d, eps);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// KV deviation: one wavefront per candidate token; 4 rows of kv_dim elements are
+// streamed once (new K, new V, cached K, cached V), squared differences summed in
+// float and reduced across the wavefront.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void deviation_kernel(const T *__restrict__ kvnew,
+                                                        const int32_t *__restrict__ row_pos,
+                                                        int n_cand, const T *__restrict__ kc,
+                                                        const T *__restrict__ vc, int kv_dim,
+                                                        float *__restrict__ dev) {
+  using V = Vec16<T>;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= n_cand) return;
+  const int lane = threadIdx.x & 63;
+  const int p = row_pos[j];
+  const int nv = kv_dim / V::N;
+  const V *kn = reinterpret_cast<const V *>(kvnew + (size_t)j * 2 * kv_dim);
+  const V *vn = kn + nv;
+  const V *ko = reinterpret_cast<const V *>(kc + (size_t)p * kv_dim);
+  const V *vo = reinterpret_cast<const V *>(vc + (size_t)p * kv_dim);
+  float acc = 0.f;
+  for (int i = lane; i < nv; i += 64) {
+    V a = kn[i], b = ko[i], c = vn[i], d = vo[i];
+#pragma unroll
+    for (int e = 0; e < V::N; ++e) {
+      float dk = a.get(e) - b.get(e), dv = c.get(e) - d.get(e);
+      acc += dk * dk + dv * dv;
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) dev[j] = acc;
+}
+hipError_t launch_deviation(int dtype, const void *kvnew, const int32_t *row_pos, int n_cand,
+                            const void *kc, const void *vc, int kv_dim, float *dev, hipStream_t s) {
+  if (n_cand == 0) return hipSuccess;
+  dim3 grid((n_cand + 3) / 4);
+  if (dtype == 0)
+    hipLaunchKernelGGL(deviation_kernel<float>, grid, dim3(256), 0, s, (const float *)kvnew, row_pos,
+                       n_cand, (const float *)kc, (const float *)vc, kv_dim, dev);
+  else
+    hipLaunchKernelGGL(deviation_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)kvnew, row_pos,
+                       n_cand, (const bf16 *)kc, (const bf16 *)vc, kv_dim, dev);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_kv_kernel(const T *__restrict__ kvnew,
+                                                         const int32_t *__restrict__ sel_rows,
+                                                         const int32_t *__restrict__ pos_out, int m,
+                                                         T *__restrict__ kc, T *__restrict__ vc,
+                                                         int kv_dim) {
+  using V = Vec16<T>;
+  const int nv = kv_dim / V::N;
+  const size_t total = (size_t)m * 2 * nv;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int r = (int)(i / (2 * nv)), c = (int)(i % (2 * nv));
+  const int src = sel_rows ? sel_rows[r] : r;
+  const int p = pos_out[r];
+  V v = reinterpret_cast<const V *>(kvnew + (size_t)src * 2 * kv_dim)[c];
+  if (c < nv)
+    reinterpret_cast<V *>(kc + (size_t)p * kv_dim)[c] = v;
+  else
+    reinterpret_cast<V *>(vc + (size_t)p * kv_dim)[c - nv] = v;
+}
+hipError_t launch_scatter_kv(int dtype, const void *kvnew, const int32_t *sel_rows,
+                             const int32_t *pos_out, int m, void *kc, void *vc, int kv_dim,
+                             hipStream_t s) {
+  if (m == 0) return hipSuccess;
+  const int vn = dtype == 0 ? 4 : 8;
+  size_t total = (size_t)m * 2 * (kv_dim / vn);
+  dim3 grid((unsigned)((total + 255) / 256));
+  if (dtype == 0)
+    hipLaunchKernelGGL(scatter_kv_kernel<float>, grid, dim3(256), 0, s, (const float *)kvnew, sel_rows,
+                       pos_out, m, (float *)kc, (float *)vc, kv_dim);
+  else
+    hipLaunchKernelGGL(scatter_kv_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)kvnew, sel_rows,
+                       pos_out, m, (bf16 *)kc, (bf16 *)vc, kv_dim);
+  return hipGetLastError();
+}
+
+}  // namespace cb

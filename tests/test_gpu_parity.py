@@ -1,0 +1,366 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same
+seeded inputs, element by element.  Protocol for selection (a one-token flip changes a
+whole cache row): (i) deviation vectors agree within tolerance, (ii) the GPU's kept set
+is bit-exact the oracle's top-k applied to the GPU's deviation vector, (iii) caches and
+hidden states are compared with the oracle forced to the GPU's kept sets."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cacheblend_oracle as O
+from workloads import synth
+from workloads.configs import ModelShape, Workload, WORKLOADS
+
+from gpu_util import (TOL, announce, cache_tensors, dev_layers, max_abs_rel, np_layers, oracle_caches,
+                      scaled_weights, to_np)
+
+pytestmark = pytest.mark.gpu
+
+F32_M = ModelShape(2, 256, 4, 2, 64, 688, 1e-5, 1e4, "f32")
+BF16_M = ModelShape(2, 512, 8, 2, 128, 1408, 1e-5, 1e6, "bf16")
+BF16_G7 = ModelShape(2, 448, 14, 2, 128, 1000, 1e-5, 5e6, "bf16")     # 7 query heads per kv head
+BF16_DH64 = ModelShape(2, 256, 4, 2, 64, 688, 1e-5, 1e4, "bf16")
+MODELS = {"f32": F32_M, "bf16": BF16_M, "bf16_g7": BF16_G7, "bf16_dh64": BF16_DH64}
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2405_16444_amd as pkg
+    return pkg
+
+
+def layer_case(model, n_tokens, n_rows, n_suffix, seed, std=0.07):
+    """Synthetic single-layer inputs: random cache, random hidden rows at sorted positions."""
+    g = torch.Generator().manual_seed(seed)
+    dt = synth.storage_dtype(model)
+    lw = scaled_weights(replace(model, n_layers=1), seed, std)[0]
+    h = synth.random_rows(n_rows, model.d_model, 1.0, seed + 1)
+    n_ctx = n_tokens - n_suffix
+    ctx_rows = torch.sort(torch.randperm(n_ctx, generator=g)[:n_rows - n_suffix]).values
+    pos = torch.cat([ctx_rows, torch.arange(n_ctx, n_tokens)]).to(torch.int32)
+    kc = synth.random_rows(n_tokens, model.kv_dim, 0.5, seed + 2, dtype=dt).view(n_tokens, model.n_kv_heads, model.head_dim)
+    vc = synth.random_rows(n_tokens, model.kv_dim, 0.5, seed + 3, dtype=dt).view(n_tokens, model.n_kv_heads, model.head_dim)
+    return lw, h, pos, kc, vc
+
+
+def run_layer_both(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, forced=None, want_dev=True):
+    ctx = P.cb_create(model, kc.shape[0])
+    dlw = dev_layers([lw])[0]
+    kg, vg = kc.cuda().contiguous(), vc.cuda().contiguous()
+    f = None if forced is None else torch.as_tensor(forced, dtype=torch.int32).cuda()
+    h_out, pos_out, dev = P.cb_fuse_layer(ctx, 0, dlw, h.cuda(), pos.cuda(), n_suffix, kg, vg, k_keep,
+                                          forced_sel=f, want_dev=want_dev)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    return h_out.cpu(), pos_out.cpu(), None if dev is None else dev.cpu(), kg.cpu(), vg.cpu()
+
+
+def oracle_layer(model, lw, h, pos, kc, vc, n_suffix, k_keep, forced):
+    rnd = O.storage_round(model.dtype)
+    ko, vo = to_np(kc), to_np(vc)
+    nlw = np_layers([lw])[0]
+    h_ref, pos_ref, dev_ref, sel_ref = O.fuse_layer(nlw, model, to_np(h), pos.numpy(), n_suffix, ko, vo,
+                                                    k_keep, forced_sel=forced, kv_round=rnd)
+    return h_ref, pos_ref, dev_ref, ko, vo
+
+
+@pytest.mark.parametrize("name,n_tokens,n_rows,n_suffix", [
+    ("f32", 300, 300, 20),          # every row present (dense causal layer), ragged tiles
+    ("f32", 333, 97, 5),            # sparse rows
+    ("bf16", 637, 637, 37),
+    ("bf16", 700, 203, 11),
+    ("bf16_g7", 419, 150, 9),
+    ("bf16_dh64", 260, 131, 3),
+    ("bf16", 130, 1, 1),            # a single (suffix) row
+    ("bf16", 200, 64, 0),           # no suffix at all
+])
+def test_layer_without_selection(P, name, n_tokens, n_rows, n_suffix):
+    model = MODELS[name]
+    announce("layer_without_selection", name, n_tokens, n_rows, n_suffix)
+    lw, h, pos, kc, vc = layer_case(model, n_tokens, n_rows, n_suffix, seed=100 + n_rows)
+    k_keep = n_rows - n_suffix
+    h_out, pos_out, _, kg, vg = run_layer_both(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, want_dev=False)
+    h_ref, pos_ref, _, ko, vo = oracle_layer(model, lw, h, pos, kc, vc, n_suffix, k_keep, None)
+    tol = TOL[model.dtype]
+    assert np.array_equal(pos_out.numpy(), pos_ref)
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    # rows that were not recomputed stay bit-identical
+    untouched = np.setdiff1d(np.arange(n_tokens), pos_ref)
+    assert torch.equal(kg[untouched], kc[untouched]) and torch.equal(vg[untouched], vc[untouched])
+    assert max_abs_rel(to_np(h_out), h_ref) < tol
+
+
+@pytest.mark.parametrize("name,n_tokens,n_rows,n_suffix,k_keep", [
+    ("f32", 333, 333, 13, 96),
+    ("f32", 333, 120, 13, 31),
+    ("bf16", 700, 700, 44, 197),
+    ("bf16", 700, 260, 44, 65),
+    ("bf16_g7", 419, 300, 9, 77),
+    ("bf16", 300, 150, 10, 0),      # nothing kept: suffix rows only
+    ("bf16", 300, 150, 0, 40),      # no suffix
+    ("f32", 100, 50, 0, 0),         # nothing survives
+])
+def test_layer_with_selection(P, name, n_tokens, n_rows, n_suffix, k_keep):
+    model = MODELS[name]
+    announce("layer_with_selection", name, n_tokens, n_rows, n_suffix, k_keep)
+    lw, h, pos, kc, vc = layer_case(model, n_tokens, n_rows, n_suffix, seed=500 + n_rows + k_keep)
+    h_out, pos_out, dev, kg, vg = run_layer_both(P, model, lw, h, pos, kc, vc, n_suffix, k_keep)
+    tol = TOL[model.dtype]
+    n_cand = n_rows - n_suffix
+    # (ii) kept set == oracle top-k of the GPU's deviation vector, bit-exact
+    sel_rows = O.top_k_indices(dev.numpy(), k_keep)
+    sel_pos = pos.numpy()[:n_cand][sel_rows]
+    assert np.array_equal(pos_out.numpy()[:k_keep], sel_pos)
+    assert np.array_equal(pos_out.numpy()[k_keep:], pos.numpy()[n_cand:])
+    # (i) + (iii) oracle forced to that set
+    h_ref, pos_ref, dev_ref, ko, vo = oracle_layer(model, lw, h, pos, kc, vc, n_suffix, k_keep, sel_pos)
+    assert max_abs_rel(dev.numpy(), dev_ref) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    untouched = np.setdiff1d(np.arange(n_tokens), pos_ref)
+    assert torch.equal(kg[untouched], kc[untouched]) and torch.equal(vg[untouched], vc[untouched])
+    assert h_out.shape[0] == k_keep + n_suffix
+    if h_out.shape[0]:
+        assert max_abs_rel(to_np(h_out), h_ref) < tol
+    # forcing the same set through the ABI reproduces the free run bit for bit
+    if k_keep:
+        h2, pos2, dev2, kg2, vg2 = run_layer_both(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, forced=sel_pos)
+        assert torch.equal(h2, h_out) and torch.equal(pos2, pos_out) and torch.equal(kg2, kg)
+
+
+def test_top_k_ties_go_to_lower_position(P):
+    """Exact ties: Wk = 0 and a zero K cache remove K from the deviation, and groups of
+    identical hidden rows over identical V rows give identical V deviations."""
+    model = F32_M
+    announce("top_k_ties")
+    n_tokens, n_suffix = 2100, 4
+    n_rows = n_tokens
+    lw, h, pos, kc, vc = layer_case(model, n_tokens, n_rows, n_suffix, seed=77)
+    lw["wk"].zero_()
+    kc.zero_()
+    h[:n_tokens - n_suffix] = h[:7].repeat(300, 1)[:n_tokens - n_suffix]   # 7 distinct rows, cycling
+    vc[:] = vc[0]
+    for k_keep in (1, 299, 300, 301, 1000, 2095):
+        h_out, pos_out, dev, _, _ = run_layer_both(P, model, lw, h, pos, kc, vc, n_suffix, k_keep)
+        d = dev.numpy()
+        assert len(np.unique(d)) <= 7                                     # ties are exact
+        assert np.array_equal(pos_out.numpy()[:k_keep], O.top_k_indices(d, k_keep))
+
+
+@pytest.mark.parametrize("name", ["f32", "bf16", "bf16_dh64"])
+def test_realign_matches_oracle_and_direct_keys(P, name):
+    model = replace(MODELS[name], n_layers=3)
+    announce("realign", name)
+    lens = (37, 1, 130, 64, 9)
+    C = sum(lens)
+    dt = synth.storage_dtype(model)
+    ks = [synth.random_rows(C + 5, model.kv_dim, 1.0, 900 + l, dtype=dt).view(C + 5, model.n_kv_heads, model.head_dim)
+          for l in range(3)]
+    ctx = P.cb_create(model, C + 5)
+    kg = [k.cuda().contiguous() for k in ks]
+    off = np.concatenate([[0], np.cumsum(lens)]).tolist()
+    P.cb_realign_rope(ctx, kg, 1, 3, off)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    rnd = O.storage_round(model.dtype)
+    assert torch.equal(kg[0].cpu(), ks[0])                                  # layer outside the range
+    for l in (1, 2):
+        ref = O.realign_keys(to_np(ks[l][:C]), lens, model, rnd)
+        got = kg[l].cpu()
+        assert max_abs_rel(to_np(got[:C]), ref) < TOL[model.dtype] * (0.01 if model.dtype == "f32" else 1)
+        assert torch.equal(got[:lens[0]], ks[l][:lens[0]])                  # chunk 0 untouched
+        assert torch.equal(got[C:], ks[l][C:])                              # rows past the context
+
+
+def test_realign_many_chunks_and_layers(P):
+    model = replace(BF16_DH64, n_layers=40)
+    announce("realign_many")
+    lens = tuple(3 + (i * 7) % 11 for i in range(150))                     # 150 ragged chunks
+    C = sum(lens)
+    dt = torch.bfloat16
+    base = synth.random_rows(C, model.kv_dim, 1.0, 31, dtype=dt).view(C, model.n_kv_heads, model.head_dim)
+    kg = [base.clone().cuda() for _ in range(40)]
+    ctx = P.cb_create(model, C)
+    P.cb_realign_rope(ctx, kg, 0, 40, np.concatenate([[0], np.cumsum(lens)]).tolist())
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    ref = O.realign_keys(to_np(base), lens, model, O.round_bf16)
+    assert max_abs_rel(to_np(kg[0].cpu()), ref) < TOL["bf16"]
+    for l in (1, 31, 32, 39):
+        assert torch.equal(kg[l], kg[0])
+
+
+# ------------------------------------------------------------------ end to end
+def e2e_case(model, chunk_lens, n_suffix, seed, std=0.07):
+    w = Workload("e2e", model, tuple(chunk_lens), n_suffix, 0.15, 0.30, seed, seed + 1)
+    layers = scaled_weights(model, w.seed_weights, std)
+    x = synth.hidden_inputs(w)
+    npl, xn = np_layers(layers), synth.to_f64(x)
+    kpre, vpre = oracle_caches(w, npl, xn)
+    return w, layers, x, npl, xn, kpre, vpre
+
+
+def run_prefill(P, w, layers, x, kpre, vpre, keep, forced=None):
+    ctx = P.cb_create(w.model, w.n_tokens)
+    kg, vg = cache_tensors(w, kpre, vpre)
+    f = None if forced is None else [None if s is None else torch.as_tensor(s, dtype=torch.int32).cuda() for s in forced]
+    out = P.cb_fuse_prefill(ctx, dev_layers(layers), x.cuda(), w.chunk_lens, w.n_suffix, kg, vg, keep,
+                            forced_sel=f, want_sel=True, want_dev=True)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    return out, kg, vg
+
+
+def check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, tol):
+    rnd = O.storage_round(w.model.dtype)
+    sel_gpu = [s.cpu().numpy().astype(np.int64) for s in out.sel]
+    cand = np.arange(w.n_ctx)
+    for l, k in enumerate(keep):
+        if k < len(cand):                       # a check layer: (ii) bit-exact top-k of the GPU's vector
+            d = out.dev[l].cpu().numpy()
+            assert np.array_equal(sel_gpu[l], cand[O.top_k_indices(d, k)]), f"layer {l}"
+        else:
+            assert np.array_equal(sel_gpu[l], cand)
+        cand = sel_gpu[l]
+    ref = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep,
+                         forced_sel=sel_gpu, kv_round=rnd)
+    for l in range(w.model.n_layers):
+        if keep[l] < (w.n_ctx if l == 0 else keep[l - 1]):
+            assert max_abs_rel(out.dev[l].cpu().numpy(), ref.dev[l]) < tol, f"dev layer {l}"
+        assert max_abs_rel(to_np(kg[l].cpu()), ref.K[l]) < tol, f"K layer {l}"
+        assert max_abs_rel(to_np(vg[l].cpu()), ref.V[l]) < tol, f"V layer {l}"
+    assert max_abs_rel(to_np(out.final_hidden.cpu()), ref.final_hidden) < tol
+    return ref, sel_gpu
+
+
+def test_workload_tiny_end_to_end(P):
+    """BASELINE workload 1 exactly: 2 layers, 4 x 128 tokens + 32, keep [512, 154], float."""
+    w = WORKLOADS["tiny"]
+    announce("tiny end to end")
+    layers = synth.model_weights(w.model, w.seed_weights)
+    x = synth.hidden_inputs(w)
+    npl, xn = np_layers(layers), synth.to_f64(x)
+    kpre, vpre = oracle_caches(w, npl, xn)
+    keep = O.default_schedule(w.model.n_layers, w.n_ctx, w.ratio, w.ratio_first)
+    assert keep == P.cb_default_schedule(w.model.n_layers, w.n_ctx, w.ratio, w.ratio_first) == [512, 154]
+    out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, keep)
+    ref, sel = check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, TOL["f32"])
+    # the free-running oracle picks the same tokens here (informational overlap, asserted loosely)
+    free = O.fuse_prefill(xn, npl, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep)
+    overlap = len(set(free.sel[1]) & set(sel[1])) / keep[1]
+    print("tiny: Jaccard-style overlap of kept sets, GPU vs free oracle:", overlap)
+    assert overlap > 0.95
+
+
+@pytest.mark.parametrize("name,lens,n_suffix,keep_frac", [
+    ("f32", (60, 45, 70, 33), 7, (1.0, 0.4, 0.2)),
+    ("bf16", (150, 97, 200), 21, (1.0, 0.35, 0.15)),
+    ("bf16_g7", (80, 120, 90), 10, (1.0, 0.3, 0.3)),      # second selective layer has no check
+])
+def test_prefill_three_layers(P, name, lens, n_suffix, keep_frac):
+    model = replace(MODELS[name], n_layers=3)
+    announce("prefill_three_layers", name, lens)
+    w, layers, x, npl, xn, kpre, vpre = e2e_case(model, lens, n_suffix, seed=40)
+    keep = [int(np.ceil(f * w.n_ctx)) for f in keep_frac]
+    out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, keep)
+    ref, sel = check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, TOL[model.dtype])
+    assert set(sel[2]) <= set(sel[1])
+    # chunk 0 is a prefix: nothing in it is ever the most deviating (its deviation is rounding noise)
+    d1 = out.dev[1].cpu().numpy()
+    assert d1[:lens[0]].max() < (1e-6 if model.dtype == "f32" else 0.05) * d1[lens[0]:].max()
+
+
+@pytest.mark.parametrize("name", ["f32", "bf16"])
+def test_ratio_one_is_full_prefill_and_ratio_zero_is_plain_reuse(P, name):
+    model = replace(MODELS[name], n_layers=3)
+    announce("ratio one / zero", name)
+    w, layers, x, npl, xn, kpre, vpre = e2e_case(model, (70, 50, 90), 12, seed=60)
+    rnd, tol = O.storage_round(model.dtype), TOL[model.dtype]
+    C, S = w.n_ctx, w.n_suffix
+    # ratio 1: equals a plain causal prefill of the concatenation
+    out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, [C, C, C])
+    fk, fv, fh = O.full_prefill(xn, npl, model, rnd)
+    for l in range(3):
+        assert max_abs_rel(to_np(kg[l].cpu()), fk[l]) < tol and max_abs_rel(to_np(vg[l].cpu()), fv[l]) < tol
+    assert max_abs_rel(to_np(out.final_hidden.cpu()), fh[-S:]) < tol
+    # ratio 0: context rows of layers >= 1 are exactly the re-aligned cached rows
+    out0, kg0, vg0 = run_prefill(P, w, layers, x, kpre, vpre, [C, 0, 0])
+    ctx = P.cb_create(model, w.n_tokens)
+    kre, _ = cache_tensors(w, kpre, vpre)
+    P.cb_realign_rope(ctx, kre, 0, 3, np.concatenate([[0], np.cumsum(w.chunk_lens)]).tolist())
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    for l in (1, 2):
+        assert torch.equal(kg0[l][:C], kre[l][:C])
+        assert torch.equal(vg0[l][:C].cpu(), torch.from_numpy(vpre[l]).to(vg0[l].dtype))
+    ref0 = O.fuse_prefill(xn, npl, model, w.chunk_lens, S, kpre, vpre, [C, 0, 0], kv_round=rnd)
+    assert max_abs_rel(to_np(out0.final_hidden.cpu()), ref0.final_hidden) < tol
+    for l in range(3):
+        assert max_abs_rel(to_np(kg0[l].cpu()), ref0.K[l]) < tol
+
+
+def test_layer_calls_equal_one_prefill_call_bitwise(P):
+    model = replace(BF16_M, n_layers=3)
+    announce("layer calls == prefill call")
+    w, layers, x, npl, xn, kpre, vpre = e2e_case(model, (100, 140, 60), 9, seed=80)
+    keep = [w.n_ctx, 90, 40]
+    out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, keep)
+    ctx = P.cb_create(model, w.n_tokens)
+    k2, v2 = cache_tensors(w, kpre, vpre)
+    dl = dev_layers(layers)
+    P.cb_realign_rope(ctx, k2, 0, 3, np.concatenate([[0], np.cumsum(w.chunk_lens)]).tolist())
+    h = x.cuda().float()
+    pos = torch.arange(w.n_tokens, dtype=torch.int32, device="cuda")
+    for l in range(3):
+        h, pos, _ = P.cb_fuse_layer(ctx, l, dl[l], h, pos, w.n_suffix, k2[l], v2[l], keep[l])
+        assert torch.equal(pos[:keep[l]], out.sel[l])
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    assert torch.equal(h[-w.n_suffix:], out.final_hidden)
+    for l in range(3):
+        assert torch.equal(k2[l], kg[l]) and torch.equal(v2[l], vg[l])
+
+
+def test_producer_chunk_prefill_matches_oracle(P):
+    """The chunk caches made on the GPU (setup step of the bench) equal the oracle's KV^pre."""
+    from paper_2405_16444_amd import producer
+    model = replace(BF16_M, n_layers=2)
+    announce("producer")
+    w, layers, x, npl, xn, kpre, vpre = e2e_case(model, (130, 67, 150), 5, seed=90)
+    ctx = P.cb_create(model, w.n_tokens)
+    ks, vs = producer.chunk_prefill(ctx, dev_layers(layers), x.cuda()[:w.n_ctx], w.chunk_lens, w.n_tokens)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    for l in range(2):
+        assert max_abs_rel(to_np(ks[l][:w.n_ctx].cpu()), kpre[l]) < TOL["bf16"]
+        assert max_abs_rel(to_np(vs[l][:w.n_ctx].cpu()), vpre[l]) < TOL["bf16"]
+
+
+def test_error_codes_leave_buffers_untouched(P):
+    from paper_2405_16444_amd.binding import CacheBlendError
+    model = F32_M
+    announce("error codes")
+    with pytest.raises(CacheBlendError) as e:
+        P.cb_create(replace(model, head_dim=96), 64)
+    assert e.value.status == -4
+    with pytest.raises(CacheBlendError):
+        P.cb_create(replace(model, n_q_heads=5), 64)
+    lw, h, pos, kc, vc = layer_case(model, 100, 40, 4, seed=5)
+    ctx = P.cb_create(model, 100)
+    dlw = dev_layers([lw])[0]
+    kg, vg = kc.cuda(), vc.cuda()
+    for kwargs, status in [(dict(k_keep=37), -1), (dict(k_keep=-1), -1), (dict(layer=2), -1)]:
+        with pytest.raises(CacheBlendError) as e:
+            P.cb_fuse_layer(ctx, kwargs.get("layer", 0), dlw, h.cuda(), pos.cuda(), 4, kg, vg,
+                            kwargs.get("k_keep", 10))
+        assert e.value.status == status
+    with pytest.raises(CacheBlendError) as e:
+        P.cb_fuse_layer(ctx, 0, dlw, h.cuda(), pos.cuda(), 4, kg, vg, 10,
+                        workspace=torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -3
+    with pytest.raises(CacheBlendError):
+        P.cb_realign_rope(ctx, [kg, kg], 0, 2, [0, 50, 40])
+    torch.cuda.synchronize()
+    assert torch.equal(kg.cpu(), kc) and torch.equal(vg.cpu(), vc)
+    P.cb_destroy(ctx)
