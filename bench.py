@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-prefill hot path on one MI355X.
+
+A step = one cb_fuse_prefill call: re-alignment of the cached keys of every layer,
+then all L layers of selective recompute, on a synthetic request of the workload's
+shape (weights, inputs and the pre-computed chunk caches are resident in HBM before
+the timed region; the caches are restored from a pristine copy between steps, outside
+the timed region, because the path fuses them in place).
+
+Prints ONE JSON line: the whole-call throughput in recomputed token-layers per second
+(sum over layers of the rows that went through attention + MLP, divided by the call
+time = TTFT), the roofline position of the dominant kernel class (the MFMA GEMMs)
+measured with HIP events inside the library, and the CPU oracle timed on a bounded
+slice of the same workload."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="mistral7b")
+    ap.add_argument("--layers", type=int, default=0, help="reduce depth (0 = the workload's own)")
+    ap.add_argument("--ratio", type=float, default=None)
+    ap.add_argument("--flat", action="store_true", help="flat schedule instead of gradual filtering")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    return ap.parse_args()
+
+
+def attention_flops(model, sel_sets, n_ctx, n_suffix):
+    """4 * Hq * dh * sum over processed rows of (position + 1), per layer."""
+    import numpy as np
+    suffix = np.arange(n_ctx, n_ctx + n_suffix, dtype=np.float64)
+    total = 0.0
+    for sel in sel_sets:
+        pos = np.concatenate([sel.astype(np.float64), suffix])
+        total += 4.0 * model.n_q_heads * model.head_dim * float(np.sum(pos + 1.0))
+    return total
+
+
+def cpu_baseline(w, keep):
+    """The oracle as it stands on layers 0-1 of the workload (a full layer, then the first
+    selective layer with its check), real widths, synthetic inputs from the same generator."""
+    import numpy as np
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle import cacheblend_oracle as O
+    from workloads import synth
+    from dataclasses import replace
+
+    m2 = replace(w.model, n_layers=2)
+    rnd = O.storage_round(w.model.dtype)
+    layers = [{k: synth.to_f64(v) for k, v in synth.layer_weights(m2, l, w.seed_weights).items()}
+              for l in range(2)]
+    x = synth.to_f64(synth.hidden_inputs(w))
+    dt = synth.storage_dtype(w.model)
+    kpre = [synth.to_f64(synth.random_rows(w.n_ctx, m2.kv_dim, 0.5, 77 + l, dtype=dt)).reshape(
+        w.n_ctx, m2.n_kv_heads, m2.head_dim) for l in range(2)]
+    vpre = [synth.to_f64(synth.random_rows(w.n_ctx, m2.kv_dim, 0.5, 87 + l, dtype=dt)).reshape(
+        w.n_ctx, m2.n_kv_heads, m2.head_dim) for l in range(2)]
+    keep2 = [keep[0], keep[1] if len(keep) > 1 else keep[0]]
+    t0 = time.perf_counter()
+    out = O.fuse_prefill(x, layers, m2, w.chunk_lens, w.n_suffix, kpre, vpre, keep2, kv_round=rnd)
+    dt_s = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    rows = sum(out.rows)
+    return {"value": rows / dt_s, "unit": "token-layers/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"layers 0-1 of the workload at real width (full layer on {out.rows[0]} rows, then "
+                      f"K/V check on {out.rows[0]} rows and recompute of {out.rows[1]} rows), numpy float64, "
+                      f"{dt_s:.1f} s"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from dataclasses import replace
+    import paper_2405_16444_amd as P
+    from paper_2405_16444_amd import producer
+    from workloads import synth
+    from workloads.configs import WORKLOADS
+
+    w = WORKLOADS[a.workload]
+    if a.layers:
+        w = w.with_layers(a.layers)
+    if a.ratio is not None:
+        w = w.with_ratio(a.ratio)
+    m = w.model
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L, C, S, T = m.n_layers, w.n_ctx, w.n_suffix, w.n_tokens
+    keep = P.cb_default_schedule(L, C, w.ratio, w.ratio_first, a.flat)
+
+    # ---- setup (untimed): weights, inputs, pre-computed chunk caches ----
+    layers = [synth.layer_weights(m, l, w.seed_weights, device=dev) for l in range(L)]
+    x = synth.hidden_inputs(w, device=dev)
+    ctx = P.cb_create(m, T)
+    k_pre, v_pre = producer.chunk_prefill(ctx, layers, x[:C], w.chunk_lens, T)
+    torch.cuda.synchronize()
+    k_work = [t.clone() for t in k_pre]
+    v_work = [t.clone() for t in v_pre]
+
+    def restore():
+        for dst, src in zip(k_work, k_pre):
+            dst.copy_(src)
+        for dst, src in zip(v_work, v_pre):
+            dst.copy_(src)
+
+    out = P.cb_fuse_prefill(ctx, layers, x, w.chunk_lens, S, k_work, v_work, keep, want_sel=True)
+    torch.cuda.synchronize()
+    sel_sets = [s.cpu().numpy() for s in out.sel]
+    bench_out = None
+    ws, structs = out.workspace, out.weight_structs
+
+    def step():
+        nonlocal bench_out
+        bench_out = P.cb_fuse_prefill(ctx, layers, x, w.chunk_lens, S, k_work, v_work, keep,
+                                      workspace=ws, weight_structs=structs, out=bench_out)
+
+    for _ in range(a.warmup):
+        restore()
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    gpu_ms, wall_ms = [], []
+    for _ in range(a.steps):
+        restore()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        step()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall_ms.append((time.perf_counter() - t0) * 1e3)
+        gpu_ms.append(ev0.elapsed_time(ev1))
+    ms_per_step = float(np.sum(wall_ms) / a.steps)          # host clock around launch + completion
+    rows = [k + S for k in keep]
+    token_layers = float(sum(rows))
+
+    # ---- per-kernel-class times (HIP events around every launch, separate pass) ----
+    classes, roofline = {}, None
+    if not a.no_profile:
+        P.cb_profile_enable(ctx, True)
+        n_prof = max(1, min(3, a.steps))
+        for _ in range(n_prof):
+            restore()
+            step()
+        torch.cuda.synchronize()
+        prof = P.cb_profile_read(ctx)
+        P.cb_profile_enable(ctx, False)
+        prof["attention"]["flops"] = attention_flops(m, sel_sets, C, S) * n_prof
+        es = 2 if m.dtype == "bf16" else 4
+        prof["attention"]["bytes"] = 2.0 * T * m.kv_dim * es * L * n_prof   # K and V of a layer streamed once
+        for c, v in prof.items():
+            if v["launches"]:
+                classes[c] = {"ms_per_step": v["ms"] / n_prof, "launches_per_step": v["launches"] // n_prof,
+                              "tflops": v["flops"] / v["ms"] / 1e9 if v["ms"] else 0.0,
+                              "gbs": v["bytes"] / v["ms"] / 1e6 if v["ms"] else 0.0}
+        g = prof["gemm"]
+        achieved = g["flops"] / g["ms"] / 1e9
+        roofline = {"kernel": "gemm_bf16_kernel (all epilogues)", "bound": "mfma", "achieved": achieved,
+                    "peak": PEAK["mfma_bf16_tflops"], "unit": "TFLOP/s", "frac": achieved / PEAK["mfma_bf16_tflops"],
+                    "traffic": None,
+                    "avg_launch_us": g["ms"] / g["launches"] * 1e3,
+                    "flops_per_launch": g["flops"] / g["launches"]}
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        cpu = cpu_baseline(w, keep)
+
+    P.cb_destroy(ctx)
+    res = {
+        "metric": "hkvd_recompute_tokens_per_s (token-layers recomputed per second over one fused prefill)",
+        "value": token_layers / (ms_per_step * 1e-3), "unit": "token-layers/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "ttft_ms": ms_per_step, "ttft_ms_gpu_events_median": float(np.median(gpu_ms)),
+        "context_tokens_per_s": C / (ms_per_step * 1e-3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "layers": L, "d_model": m.d_model, "heads": f"{m.n_q_heads}/{m.n_kv_heads}x{m.head_dim}",
+                   "d_ff": m.d_ff, "chunks": f"{len(w.chunk_lens)}x{w.chunk_lens[0]}" if len(set(w.chunk_lens)) == 1
+                   else f"{len(w.chunk_lens)} ragged", "n_ctx": C, "n_suffix": S, "ratio": w.ratio,
+                   "schedule": "flat" if a.flat else "gradual", "keep_first": keep[1] if L > 1 else C,
+                   "keep_last": keep[-1], "token_layers": token_layers},
+        "roofline": roofline, "cpu_baseline": cpu, "kernel_classes": classes,
+    }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -139,7 +139,7 @@ def finish_block(h_rows, attn_out, lw, m):
     """Everything after attention: output projection + residual, then the
     SwiGLU MLP + residual ("multiple neural layers", Sec. 2)."""
     n = h_rows.shape[0]
-    h = h_rows + attn_out.reshape(n, -1) @ lw["wo"].T
+    h = h_rows + attn_out.reshape(n, m.n_q_heads * m.head_dim) @ lw["wo"].T
     y = rms_norm(h, lw["mlp_norm"], m.rms_eps)
     return h + (silu(y @ lw["w_gate"].T) * (y @ lw["w_up"].T)) @ lw["w_down"].T
 

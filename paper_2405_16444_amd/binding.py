@@ -184,8 +184,8 @@ def cb_fuse_layer(ctx: Context, layer: int, weights: Dict[str, torch.Tensor], h_
         assert forced_sel.dtype == torch.int32 and forced_sel.numel() == k_keep and forced_sel.is_contiguous()
     n_out = k_keep + n_suffix
     # at least one row is allocated so that the pointers are never NULL
-    h_out = torch.empty((max(1, n_out), ctx.model.d_model), dtype=torch.float32, device=dev_)[:n_out]
-    pos_out = torch.empty((max(1, n_out),), dtype=torch.int32, device=dev_)[:n_out]
+    h_out = torch.empty((max(1, n_out), ctx.model.d_model), dtype=torch.float32, device=dev_)
+    pos_out = torch.empty((max(1, n_out),), dtype=torch.int32, device=dev_)
     dev = torch.zeros((n_rows - n_suffix,), dtype=torch.float32, device=dev_) if want_dev else None
     if workspace is None:
         workspace = torch.empty(max(1, cb_layer_workspace_bytes(ctx, max(1, n_rows))), dtype=torch.uint8,
@@ -195,7 +195,7 @@ def cb_fuse_layer(ctx: Context, layer: int, weights: Dict[str, torch.Tensor], h_
                               _ptr(k_cache), _ptr(v_cache), k_cache.shape[0], k_keep, _ptr(forced_sel),
                               _ptr(h_out), _ptr(pos_out), _ptr(dev), _ptr(workspace), workspace.numel(),
                               _stream(stream)), "cb_fuse_layer")
-    return h_out, pos_out, dev
+    return h_out[:n_out], pos_out[:n_out], dev
 
 
 def cb_fuse_prefill(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: torch.Tensor,
@@ -219,14 +219,16 @@ def cb_fuse_prefill(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: 
         weight_structs = (_LayerWeights * L)(*[_weights_struct(lw, ctx.dtype, dev_) for lw in layers])
     if out is None:
         out = SimpleNamespace()
-        out.final_hidden = torch.empty((max(1, n_suffix), d), dtype=torch.float32, device=dev_)[:n_suffix]
+        out._final_buf = torch.empty((max(1, n_suffix), d), dtype=torch.float32, device=dev_)
+        out.final_hidden = out._final_buf[:n_suffix]
         out.sel = out.dev = None
         if want_sel:
-            out.sel = [torch.empty((max(1, int(k)),), dtype=torch.int32, device=dev_)[:int(k)]
-                       for k in keep_counts]
+            out._sel_buf = [torch.empty((max(1, int(k)),), dtype=torch.int32, device=dev_) for k in keep_counts]
+            out.sel = [b[:int(k)] for b, k in zip(out._sel_buf, keep_counts)]
         if want_dev:
             cand = [n_ctx] + [int(k) for k in keep_counts[:-1]]
-            out.dev = [torch.zeros((max(1, c),), dtype=torch.float32, device=dev_)[:c] for c in cand]
+            out._dev_buf = [torch.zeros((max(1, c),), dtype=torch.float32, device=dev_) for c in cand]
+            out.dev = [b[:c] for b, c in zip(out._dev_buf, cand)]
     if workspace is None:
         workspace = torch.empty(cb_prefill_workspace_bytes(ctx, T), dtype=torch.uint8, device=dev_)
     forced_arr = None
@@ -234,11 +236,11 @@ def cb_fuse_prefill(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: 
         for l, f in enumerate(forced_sel):
             assert f is None or (f.dtype == torch.int32 and f.numel() == keep_counts[l] and f.is_contiguous())
         forced_arr = _ptr_array(forced_sel)
-    sel_arr = _ptr_array(out.sel) if out.sel is not None else None
-    dev_arr = _ptr_array(out.dev) if out.dev is not None else None
+    sel_arr = _ptr_array(out._sel_buf) if out.sel is not None else None
+    dev_arr = _ptr_array(out._dev_buf) if out.dev is not None else None
     _check(_lib.cb_fuse_prefill(ctx._h, weight_structs, _ptr(x), _i32_array(chunk_lens), len(chunk_lens),
                                 n_suffix, _ptr_array(k_cache_layers), _ptr_array(v_cache_layers),
-                                _i32_array(keep_counts), forced_arr, _ptr(out.final_hidden), sel_arr,
+                                _i32_array(keep_counts), forced_arr, _ptr(out._final_buf), sel_arr,
                                 dev_arr, _ptr(workspace), workspace.numel(), _stream(stream)),
            "cb_fuse_prefill")
     out.workspace = workspace

@@ -385,6 +385,16 @@ def test_error_shrinks_with_ratio_report_only():
     assert errs[-1] < 1e-10 and errs[0] > errs[-1]
 
 
+def test_empty_survivor_set_is_handled():
+    w = SMALL_W
+    layers, npl, x, xn, kpre, vpre = setup_fuse(w)
+    lw = npl[1]
+    kc = np.zeros((w.n_tokens, 2, 8)); vc = np.zeros_like(kc)
+    h, pos, dev, sel = O.fuse_layer(lw, w.model, xn[:10], np.arange(10), 0, kc, vc, 0)
+    assert h.shape == (0, 32) and len(pos) == 0 and len(sel) == 0 and dev.shape == (10,)
+    assert not kc.any() and not vc.any()
+
+
 def test_bf16_mode_rounds_cache_rows_only():
     w = Workload("b", replace(SMALL, dtype="bf16"), (5, 7, 6), 3, 0.3, 0.5, 11, 12)
     layers, npl, x, xn = make(w, 0.3)
