@@ -154,7 +154,8 @@ int cb_fuse_prefill(cb_ctx *ctx, const cb_layer_weights *layers, const void *x,
 
 /* Per-kernel-class timing for benchmarks.  Classes: */
 enum { CB_PROF_GEMM = 0, CB_PROF_ATTN = 1, CB_PROF_REALIGN = 2, CB_PROF_DEV = 3,
-       CB_PROF_TOPK = 4, CB_PROF_NORM = 5, CB_PROF_OTHER = 6, CB_PROF_NCLASS = 7 };
+       CB_PROF_TOPK = 4, CB_PROF_NORM = 5, CB_PROF_OTHER = 6, CB_PROF_REDUCE = 7,
+       CB_PROF_NCLASS = 8 };
 /* enable != 0: every later launch on ctx is bracketed by a pair of HIP events on
  * its stream (this slows the pass a little; do not time whole calls meanwhile). */
 int cb_profile_enable(cb_ctx *ctx, int32_t enable);

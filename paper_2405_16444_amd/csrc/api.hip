@@ -232,6 +232,10 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
                  ((double)q_dim * d + (double)rows * q_dim) * es + (double)rows * d * 8);
     CB_HIP(launch_gemm(f, s));
   }
+  if (gemm_needs_reduce(f)) {
+    ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+    CB_HIP(launch_gemm_reduce(f, s));
+  }
   {
     ProfScope ps(c, s, CB_PROF_NORM, 0, (double)rows * d * (4 + es));
     CB_HIP(launch_rmsnorm(dt, ws.hmid, w->mlp_norm, ws.xn, rows, d, m.rms_eps, s));
@@ -251,6 +255,10 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * F * d,
                  ((double)F * d + (double)rows * F) * es + (double)rows * d * 8);
     CB_HIP(launch_gemm(f, s));
+  }
+  if (gemm_needs_reduce(f)) {
+    ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+    CB_HIP(launch_gemm_reduce(f, s));
   }
   return CB_OK;
 }

@@ -334,9 +334,10 @@ static void launch_typed(int dtype, dim3 grid, const GemmParams &p, hipStream_t 
   }
 }
 
-hipError_t launch_gemm(const GemmArgs &g, hipStream_t s) {
-  if (g.M == 0) return hipSuccess;
-  GemmParams p = {};
+// Fills the kernel parameters and the launch grid for a problem.
+static void plan_gemm(const GemmArgs &g, GemmParams *pp, dim3 *grid) {
+  GemmParams &p = *pp;
+  p = GemmParams{};
   p.a = g.a; p.lda = g.lda; p.a_rows = g.a_rows; p.M = g.M; p.K = g.K;
   p.n_seg = g.epi == EPI_SEG ? g.n_seg : 1;
   p.nb[0] = 0;
@@ -359,19 +360,37 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t s) {
       else p.k_per_split = ceil_div(ceil_div(g.K, p.splits), bk) * bk;
     }
   }
-  dim3 grid(ceil_div(p.N, oc), ceil_div(g.M, bm), p.splits);
+  *grid = dim3(ceil_div(p.N, oc), ceil_div(g.M, bm), p.splits);
+}
+
+bool gemm_needs_reduce(const GemmArgs &g) {
+  if (g.M == 0 || g.epi != EPI_F32) return false;
+  GemmParams p;
+  dim3 grid;
+  plan_gemm(g, &p, &grid);
+  return p.splits > 1;
+}
+
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t s) {
+  if (g.M == 0) return hipSuccess;
+  GemmParams p;
+  dim3 grid;
+  plan_gemm(g, &p, &grid);
   if (g.epi == EPI_SEG) launch_typed<EPI_SEG>(g.dtype, grid, p, s);
   else if (g.epi == EPI_SWIGLU) launch_typed<EPI_SWIGLU>(g.dtype, grid, p, s);
   else launch_typed<EPI_F32>(g.dtype, grid, p, s);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (g.epi == EPI_F32 && p.splits > 1) {
-    size_t total4 = (size_t)g.M * p.N / 4;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s,
-                       g.partial, p.splits, g.M, p.N, g.resid, g.resid_rows, g.out_f32);
-    e = hipGetLastError();
-  }
-  return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
+  if (!gemm_needs_reduce(g)) return hipSuccess;
+  GemmParams p;
+  dim3 grid;
+  plan_gemm(g, &p, &grid);
+  size_t total4 = (size_t)g.M * p.N / 4;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s,
+                     g.partial, p.splits, g.M, p.N, g.resid, g.resid_rows, g.out_f32);
+  return hipGetLastError();
 }
 
 }  // namespace cb

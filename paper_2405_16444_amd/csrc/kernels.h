@@ -68,7 +68,11 @@ struct GemmArgs {
 };
 // Number of K splits launch_gemm will use for an EPI_F32 problem (for workspace sizing).
 int gemm_splits(int dtype, int M, int N, int K);
+// Main kernel.  An EPI_F32 problem that was split along K (gemm_needs_reduce) leaves partial
+// sums in g.partial and must be completed by launch_gemm_reduce on the same stream.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
+bool gemm_needs_reduce(const GemmArgs &g);
+hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s);
 
 // ---- attention.hip ---------------------------------------------------------
 // o[r, h, :] = softmax_{j <= q_pos[r]}(q[r,h,:] . K[j, h/g, :] / sqrt(dh)) V[j, h/g, :]
