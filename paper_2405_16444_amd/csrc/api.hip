@@ -81,14 +81,17 @@ struct LayerWs {
 
 size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
   const cb_model_desc &m = c->m;
-  const int bm = m.dtype == CB_BF16 ? 128 : 64;
+  const int d = m.d_model, q_dim = m.n_q_heads * m.head_dim, kv_dim = m.n_kv_heads * m.head_dim;
   size_t need = 0;
-  const int shapes[2] = {m.n_q_heads * m.head_dim, m.d_ff};
-  for (int M = 1; M <= max_rows; M = (M == max_rows) ? max_rows + 1 : std::min(max_rows, (M / bm + 1) * bm)) {
-    for (int K : shapes) {
-      int s = gemm_splits(m.dtype, M, m.d_model, K);
-      if (s > 1) need = std::max(need, (size_t)s * M * m.d_model);
-    }
+  // the split decision depends on M through the tile count only; tiles are multiples of 32 rows
+  for (int M = 32;; M += 32) {
+    const int mm = std::min(M, max_rows);
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, 2 * kv_dim, d));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim, d));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim + 2 * kv_dim, d));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, q_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, m.d_ff));
+    if (mm == max_rows) break;
   }
   return need;
 }
@@ -162,6 +165,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   }
   GemmArgs g = {};
   g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim;
+  g.partial = ws.partial; g.partial_floats = ws.partial_floats;
   const int32_t *sel_rows = nullptr;
   if (check) {
     // K/V of every row that reached this layer (Sec. 6: "newly computed KV")
@@ -173,6 +177,10 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * 2 * kv_dim,
                    ((double)2 * kv_dim * d + (double)n * d + (double)n * 2 * kv_dim) * es);
       CB_HIP(launch_gemm(g, s));
+    }
+    if (gemm_needs_reduce(g)) {
+      ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+      CB_HIP(launch_gemm_reduce(g, s));
     }
     float *dev = dev_out ? dev_out : ws.dev;
     {
@@ -199,6 +207,10 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
                    ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es);
       CB_HIP(launch_gemm(g, s));
     }
+    if (gemm_needs_reduce(g)) {
+      ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+      CB_HIP(launch_gemm_reduce(g, s));
+    }
   } else {
     // every row is kept: one fused Q|K|V projection, K and V written straight into the cache
     {
@@ -214,6 +226,10 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * (q_dim + 2 * kv_dim),
                    ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es);
       CB_HIP(launch_gemm(g, s));
+    }
+    if (gemm_needs_reduce(g)) {
+      ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+      CB_HIP(launch_gemm_reduce(g, s));
     }
   }
   {

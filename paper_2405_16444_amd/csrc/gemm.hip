@@ -2,18 +2,23 @@
 // selected tokens, then "the same attention module" and the rest of the layer).
 // C[M, N] = A[M, K] * W[N, K]^T with both operands K-contiguous.
 //
-// bf16 storage: v_mfma_f32_32x32x16_bf16, 128x128x64 tiles staged through LDS,
-// float accumulation.  float storage: plain FMA tiles (parity mode, not tuned).
+// bf16 storage: v_mfma_f32_32x32x16_bf16 with float accumulation.  The main kernel
+// (gemm_bf16_dma_kernel) streams (32*I) x 256 x 32 tiles through a 4-stage LDS ring
+// filled by direct global->LDS loads, with an XCD-aware tile order; a simpler
+// register-staged 128x128x64 kernel covers K that is not a multiple of 32.
+// float storage: plain FMA tiles (parity mode, not tuned).
 // Every kernel ends by parking its accumulator tile in LDS; one shared epilogue
 // then walks it row-major, 4 adjacent columns per lane, which gives the rotary
 // embedding its (2i, 2i+1) pair in one lane, SwiGLU its gate and up value in one
-// lane, and coalesced stores.  Epilogues:
+// lane, and coalesced stores.  A problem with too few tiles to fill 256 CUs is split
+// along K: the main kernel then stores raw partial sums and a second kernel adds them
+// in a fixed order (no atomics: bitwise reproducible) and applies the epilogue.
+// Epilogues:
 //   EPI_SEG    up to three column segments (Q | K | V), each with its own weight
 //              matrix, destination, optional destination-row map (scatter into the
 //              KV cache) and optional rotary embedding at the row's position
 //   EPI_SWIGLU silu(x Wg^T) * (x Wu^T)
-//   EPI_F32    float output (+ residual), or split-K partial sums reduced by a
-//              second kernel in a fixed order (no atomics: bitwise reproducible)
+//   EPI_F32    float output (+ residual)
 #include "common.h"
 #include "kernels.h"
 
@@ -66,61 +71,317 @@ template <> __device__ __forceinline__ void store4<bf16>(bf16 *d, float a, float
   *reinterpret_cast<bf16x4 *>(d) = v;
 }
 
-// sC: BM x (tile columns) floats, pitch `pitch`.  n0: first output column of the tile.
-template <typename T, int EPI, int BM, int BN>
-__device__ __forceinline__ void epilogue(const float *sC, int pitch, int m0, int n0, const GemmParams &p) {
+// One group of 4 adjacent output columns (gc .. gc+3) of logical row gr.
+// v: accumulated values; u: the matching "up" values (EPI_SWIGLU only).
+template <typename T, int EPI>
+__device__ __forceinline__ void apply_epilogue(float4 v, float4 u, int gr, int gc, const GemmParams &p) {
+  if (EPI == EPI_SEG) {
+    int s = 0;
+    if (p.n_seg > 1 && gc >= p.nb[1]) s = 1;
+    if (p.n_seg > 2 && gc >= p.nb[2]) s = 2;
+    const int lc = gc - p.nb[s];
+    if (p.rope[s]) {
+      const int half = p.head_dim / 2;
+      const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (lc % p.head_dim) / 2;
+      const float2 c0 = t[0], c1 = t[1];
+      float4 o;
+      o.x = v.x * c0.x - v.y * c0.y;
+      o.y = v.x * c0.y + v.y * c0.x;
+      o.z = v.z * c1.x - v.w * c1.y;
+      o.w = v.z * c1.y + v.w * c1.x;
+      v = o;
+    }
+    const int dr = p.row_map[s] ? p.row_map[s][gr] : gr;
+    store4<T>(reinterpret_cast<T *>(p.dst[s]) + (size_t)dr * p.ld[s] + lc, v.x, v.y, v.z, v.w);
+  } else if (EPI == EPI_SWIGLU) {
+    float4 o;
+    o.x = v.x / (1.f + expf(-v.x)) * u.x;
+    o.y = v.y / (1.f + expf(-v.y)) * u.y;
+    o.z = v.z / (1.f + expf(-v.z)) * u.z;
+    o.w = v.w / (1.f + expf(-v.w)) * u.w;
+    store4<T>(reinterpret_cast<T *>(p.dst[0]) + (size_t)gr * p.ld[0] + gc, o.x, o.y, o.z, o.w);
+  } else {
+    if (p.resid) {
+      const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
+      const float4 q = *reinterpret_cast<const float4 *>(p.resid + (size_t)rr * p.N + gc);
+      v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+    }
+    *reinterpret_cast<float4 *>(p.out_f32 + (size_t)gr * p.N + gc) = v;
+  }
+}
+
+// Walks `rows` x BN floats parked in LDS (pitch `pitch`); m0/n0: first logical row /
+// first output column of this block of rows; z: K-split index of the workgroup.
+template <typename T, int EPI, int BN>
+__device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int rows, int m0, int n0, int z,
+                                             const GemmParams &p) {
   constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   constexpr int GROUPS = OUT_COLS / 4;
-  for (int g = threadIdx.x; g < BM * GROUPS; g += 256) {
+  for (int g = threadIdx.x; g < rows * GROUPS; g += (int)blockDim.x) {
     const int r = g / GROUPS, c = (g % GROUPS) * 4;
     const int gr = m0 + r, gc = n0 + c;
     if (gr >= p.M || gc >= p.N) continue;
-    float4 v = *reinterpret_cast<const float4 *>(sC + r * pitch + c);
-    if (EPI == EPI_SEG) {
-      int s = 0;
-      if (p.n_seg > 1 && gc >= p.nb[1]) s = 1;
-      if (p.n_seg > 2 && gc >= p.nb[2]) s = 2;
-      const int lc = gc - p.nb[s];
-      if (p.rope[s]) {
-        const int half = p.head_dim / 2;
-        const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (lc % p.head_dim) / 2;
-        const float2 c0 = t[0], c1 = t[1];
-        float4 o;
-        o.x = v.x * c0.x - v.y * c0.y;
-        o.y = v.x * c0.y + v.y * c0.x;
-        o.z = v.z * c1.x - v.w * c1.y;
-        o.w = v.z * c1.y + v.w * c1.x;
-        v = o;
-      }
-      const int dr = p.row_map[s] ? p.row_map[s][gr] : gr;
-      store4<T>(reinterpret_cast<T *>(p.dst[s]) + (size_t)dr * p.ld[s] + lc, v.x, v.y, v.z, v.w);
-    } else if (EPI == EPI_SWIGLU) {
-      const float4 u = *reinterpret_cast<const float4 *>(sC + r * pitch + OUT_COLS + c);
-      float4 o;
-      o.x = v.x / (1.f + expf(-v.x)) * u.x;
-      o.y = v.y / (1.f + expf(-v.y)) * u.y;
-      o.z = v.z / (1.f + expf(-v.z)) * u.z;
-      o.w = v.w / (1.f + expf(-v.w)) * u.w;
-      store4<T>(reinterpret_cast<T *>(p.dst[0]) + (size_t)gr * p.ld[0] + gc, o.x, o.y, o.z, o.w);
+    const float4 v = *reinterpret_cast<const float4 *>(sC + r * pitch + c);
+    if (EPI != EPI_SWIGLU && p.splits > 1) {
+      *reinterpret_cast<float4 *>(p.partial + ((size_t)z * p.M + gr) * p.N + gc) = v;
     } else {
-      if (p.splits == 1) {
-        if (p.resid) {
-          const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
-          const float4 q = *reinterpret_cast<const float4 *>(p.resid + (size_t)rr * p.N + gc);
-          v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
-        }
-        *reinterpret_cast<float4 *>(p.out_f32 + (size_t)gr * p.N + gc) = v;
-      } else {
-        *reinterpret_cast<float4 *>(p.partial + ((size_t)blockIdx.z * p.M + gr) * p.N + gc) = v;
-      }
+      float4 u = v;
+      if (EPI == EPI_SWIGLU) u = *reinterpret_cast<const float4 *>(sC + r * pitch + OUT_COLS + c);
+      apply_epilogue<T, EPI>(v, u, gr, gc, p);
     }
   }
 }
 
 // ---------------------------------------------------------------------------
-// bf16 MFMA kernel.  4 wavefronts as 2x2, each owning a 64x64 block = 2x2 MFMA
-// tiles of 32x32.  LDS rows are padded by 16 bytes so that the 16-byte operand
-// reads of 8 consecutive lanes fall into 8 different bank groups.
+// Main bf16 kernel.
+//   tile        BM = 32*I rows (I = 2,4,6,8) x 256 columns x 64 k per stage (128-byte
+//               rows: every global request is a whole cache line)
+//   wavefronts  4 as 2 x 2, each owning (BM/2) x 128 = (I/2) x 4 MFMA tiles: the
+//               layout with the fewest LDS operand bytes per MFMA (LDS read bandwidth,
+//               not the matrix cores, limits narrower wavefront tiles).  With one
+//               wavefront per SIMD nothing else hides LDS latency, so the operand
+//               reads are issued by hand (inline ds_read_b128 + explicit
+//               s_waitcnt lgkmcnt) one k-step ahead of the MFMAs that use them.
+//   LDS rings   activation tile (BM rows x 128 bytes): 2 stages; weight tile (256 rows x
+//               128 bytes): the 3-4 stages that still fit in 160 KB -- weights stream
+//               from HBM once and need the deeper queue, activations mostly hit L2.
+//               Both are filled by global_load_lds_dwordx4 (no register staging).  A
+//               wavefront-wide load writes 1 KB contiguously (lane l -> byte 16*l),
+//               i.e. 8 rows x 8 chunks; lane l fetches global chunk (l%8) ^ f(row) of
+//               row l/8, f(r) = (r&7) ^ ((r>>3)&1), so that the later 16-byte operand
+//               reads of 8 (and of 16) consecutive rows hit distinct bank groups
+//               (XOR swizzle instead of padding).
+//   pipeline    one barrier per k-tile, placed before the LAST k-step of tile t: by
+//               then every wavefront holds its last fragments of stage t in
+//               registers, so after "tile t+1 landed" (s_waitcnt vmcnt) + barrier the
+//               stage is refilled with tile t+S and the first fragments of tile t+1
+//               are requested while the last 16 MFMAs of tile t run.  The
+//               compiler does not order LDS reads against these loads, hence the
+//               explicit waits; plain s_barrier is used because __syncthreads()
+//               would drain every outstanding load.
+//   tile order  1-D grid; workgroup id -> (xcd = id % 8, j = id / 8); an XCD walks
+//               its own n-tiles (n % 8 == xcd) with the m-tiles innermost, so the
+//               workgroups that share a weight tile run back to back on one L2.
+// Requires K % 64 == 0 and k_per_split % 64 == 0.
+// ---------------------------------------------------------------------------
+constexpr int DMA_BN = 256, DMA_BK = 64, DMA_CP = DMA_BN + 4;
+// Two rings: the activation tile (mostly L2 hits) is double-buffered, the weight tile (streamed
+// from HBM, long latency) gets every remaining stage that fits in 160 KB, up to 4.
+constexpr int DMA_SA = 2;
+constexpr int dma_w_stages(int I) {
+  const int left = 160 * 1024 - DMA_SA * 32 * I * 128;
+  return left / (DMA_BN * 128) > 4 ? 4 : left / (DMA_BN * 128);
+}
+constexpr int dma_smem_bytes(int I) {
+  const int ring = DMA_SA * 32 * I * 128 + dma_w_stages(I) * DMA_BN * 128;
+  const int park = (I < 4 ? 32 * I : 128) * DMA_CP * 4;
+  return ring > park ? ring : park;
+}
+
+#define CB_GLDS16(gptr, lptr)                                                              \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gptr), \
+                                   (__attribute__((address_space(3))) void *)(lptr), 16, 0, 0)
+
+// LDS operand read issued by hand: the result registers are valid only after a matching
+// lds_wait<N>() (N = number of younger reads that may still be in flight).
+template <int OFF> __device__ __forceinline__ void lds_read16(bf16x8 &dst, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N)); }
+// ties a fragment to the preceding wait so that no use of it is scheduled before the wait
+__device__ __forceinline__ void lds_pin(bf16x8 &f) { asm volatile("" : "+v"(f)); }
+template <int N> __device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+template <int I, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  constexpr int BM = 32 * I, SW = dma_w_stages(I);
+  constexpr int A_STAGE = BM * 128, W_STAGE = DMA_BN * 128, W_RING = DMA_SA * A_STAGE;
+  constexpr int LA = BM / 32, LW = DMA_BN / 32;          // 16-byte loads per lane per tile (8 rows x 4 waves each)
+  static_assert(SW >= 3, "the vmcnt bookkeeping below assumes at least 3 weight stages");
+  constexpr int IH = I / 2;                              // row blocks per wavefront
+  constexpr int NF = IH + 4;                             // operand reads per k-step per wavefront
+  constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? DMA_BN / 2 : DMA_BN;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;               // 2 x 2 wavefronts, (BM/2) x 128 each
+
+  // XCD-aware tile order
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int nblk = (tiles_n + 7) >> 3;
+  const int per_z = nblk * tiles_m;
+  const int z = j / per_z, rem = j - z * per_z;
+  const int nt = xcd + 8 * (rem / tiles_m), mt = rem % tiles_m;
+  if (nt >= tiles_n) return;
+  const int m0 = mt * BM, n0 = nt * OUT_COLS;
+  const int kb = z * p.k_per_split;
+  const int ke = min(p.K, kb + p.k_per_split);
+  const int nk = (ke - kb) / DMA_BK;
+
+  // global source of each of this lane's loads per tile (row pointer + swizzled chunk)
+  const bf16 *src_a[LA], *src_w[LW];
+#pragma unroll
+  for (int i = 0; i < LA; ++i) {
+    const int r = (wave + 4 * i) * 8 + (lane >> 3);           // row of the activation tile
+    const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
+    int ar = min(m0 + r, p.M - 1);
+    if (p.a_rows) ar = p.a_rows[ar];
+    src_a[i] = reinterpret_cast<const bf16 *>(p.a) + (size_t)ar * p.lda + chunk * 8 + kb;
+  }
+#pragma unroll
+  for (int i = 0; i < LW; ++i) {
+    const int r = (wave + 4 * i) * 8 + (lane >> 3);           // row of the weight tile
+    const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
+    src_w[i] = weight_row<bf16, EPI>(p, n0 + r, DMA_BN / 2, n0, r) + chunk * 8 + kb;
+  }
+  // load number idx of tile t: idx < LA activation, else weight; tile indices are clamped so
+  // that every tile issues the same number of loads
+  auto issue_one = [&](int t, int idx) {
+    if (idx < LA) {
+      const int k0 = min(t, nk - 1) * DMA_BK;
+      CB_GLDS16(src_a[idx] + k0, smem + (t % DMA_SA) * A_STAGE + (wave + 4 * idx) * 1024);
+    } else {
+      const int tw = t + SW - DMA_SA;                 // the weight ring runs SW - 2 tiles further ahead
+      const int k0 = min(tw, nk - 1) * DMA_BK;
+      CB_GLDS16(src_w[idx - LA] + k0, smem + W_RING + (tw % SW) * W_STAGE + (wave + 4 * (idx - LA)) * 1024);
+    }
+  };
+  auto issue_w = [&](int t) {
+    const int k0 = min(t, nk - 1) * DMA_BK;
+#pragma unroll
+    for (int i = 0; i < LW; ++i)
+      CB_GLDS16(src_w[i] + k0, smem + W_RING + (t % SW) * W_STAGE + (wave + 4 * i) * 1024);
+  };
+
+  f32x16 acc[IH][4];
+#pragma unroll
+  for (int i = 0; i < IH; ++i)
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][jb][r] = 0.f;
+
+  if (nk > 0) {
+    const int sw = (lane & 7) ^ ((lane >> 3) & 1), h = lane >> 5;
+    int rd[4];                                                    // k-step ks reads chunk 2*ks + h
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) rd[ks] = (lane & 31) * 128 + (((2 * ks + h) ^ sw) << 4);
+    const int a_off = (wm * IH * 32) * 128, b_off = (wn * 128) * 128;
+    bf16x8 fa[2][IH], fb[2][4];
+    constexpr int NM = IH * 4;                         // MFMAs per k-step per wavefront
+    constexpr int NL = LA + LW;                        // loads per tile per lane
+    constexpr int NSLOT = NM > NF ? NM : NF;
+    // operand read number idx (0..NF-1) into fragment buffer buf; base_w / base_a are the LDS
+    // byte addresses of this lane's first weight / activation fragment of the k-step
+    auto read_one = [&](unsigned base_w, unsigned base_a, int buf, int idx) {
+      switch (idx) {
+        case 0: lds_read16<0>(fb[buf][0], base_w); break;
+        case 1: lds_read16<4096>(fb[buf][1], base_w); break;
+        case 2: lds_read16<8192>(fb[buf][2], base_w); break;
+        case 3: lds_read16<12288>(fb[buf][3], base_w); break;
+        case 4: lds_read16<0>(fa[buf][0], base_a); break;
+        case 5: if (IH > 1) lds_read16<4096>(fa[buf][IH > 1 ? 1 : 0], base_a); break;
+        case 6: if (IH > 2) lds_read16<8192>(fa[buf][IH > 2 ? 2 : 0], base_a); break;
+        case 7: if (IH > 3) lds_read16<12288>(fa[buf][IH > 3 ? 3 : 0], base_a); break;
+        default: break;
+      }
+    };
+    const unsigned lds0 = (unsigned)(size_t)smem;
+    auto pin = [&](int buf) {
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb) lds_pin(fb[buf][jb]);
+#pragma unroll
+      for (int i = 0; i < IH; ++i) lds_pin(fa[buf][i]);
+    };
+    // One k-step: the MFMAs of fragment buffer `buf`, with the operand reads of the next k-step
+    // (tile tn, step ksn, into the other buffer) and -- when `refill` -- the global loads of the
+    // next stages slotted in between them.  A wavefront issues in order and has its SIMD to
+    // itself, so anything not placed between two MFMAs would add to the MFMA time.
+    auto step = [&](int buf, bool next_reads, int tn, int ksn, bool refill, int tl) {
+      const unsigned base_w = lds0 + W_RING + (tn % SW) * W_STAGE + b_off + rd[ksn];
+      const unsigned base_a = lds0 + (tn % DMA_SA) * A_STAGE + a_off + rd[ksn];
+#pragma unroll
+      for (int j = 0; j < NSLOT; ++j) {
+        if (j < NM)
+          acc[j / 4][j % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / 4], fb[buf][j % 4],
+                                                                     acc[j / 4][j % 4], 0, 0, 0);
+        if (refill) {
+#pragma unroll
+          for (int q = j * NL / NSLOT; q < (j + 1) * NL / NSLOT; ++q) issue_one(tl, q);
+        }
+        if (next_reads && j < NF) read_one(base_w, base_a, buf ^ 1, j);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (next_reads) {
+        lds_wait<0>();
+        pin(buf ^ 1);
+      }
+    };
+
+    // Issue order: W(0..SW-2), A(0), then at the barrier of tile t: A(t+2) and W(t+SW) interleaved
+    // (activation loads first).  When tile t+1 is needed, the only loads that may be younger than
+    // the last load of A(t+1) are the LW loads of W(t+SW-1).
+#pragma unroll
+    for (int s = 0; s < SW - 1; ++s) issue_w(s);
+#pragma unroll
+    for (int q = 0; q < LA; ++q) issue_one(0, q);
+    vm_wait<0>();
+    wg_barrier();
+#pragma unroll
+    for (int q = 0; q < NL; ++q) issue_one(1, q);
+#pragma unroll
+    for (int q = 0; q < NF; ++q) read_one(lds0 + W_RING + b_off + rd[0], lds0 + a_off + rd[0], 0, q);
+    lds_wait<0>();
+    pin(0);
+    for (int t = 0; t + 1 < nk; ++t) {
+      step(0, true, t, 1, false, 0);
+      step(1, true, t, 2, false, 0);
+      step(0, true, t, 3, false, 0);
+      // last k-step: fragments are in registers, so once tile t+1 has landed everywhere the
+      // stages of tile t can be refilled while these MFMAs run
+      vm_wait<LW>();
+      wg_barrier();
+      step(1, true, t + 1, 0, true, t + 2);
+    }
+    step(0, true, nk - 1, 1, false, 0);
+    step(1, true, nk - 1, 2, false, 0);
+    step(0, true, nk - 1, 3, false, 0);
+    step(1, false, 0, 0, false, 0);
+  }
+  // drain the clamped tail loads before the ring is reused as the parking area
+  vm_wait<0>();
+  __syncthreads();
+  float *sC = reinterpret_cast<float *>(smem);
+  // park and walk the tile in passes of at most 128 rows (LDS holds 128 x 260 floats)
+  constexpr int PASSES = (I + 3) / 4;
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps) {
+    const int i0 = ps * 4;                                   // first row block of the pass
+    const int nb = (I - i0) < 4 ? (I - i0) : 4;
+    if (ps > 0) __syncthreads();
+#pragma unroll
+    for (int i = 0; i < IH; ++i) {
+      const int ib = wm * IH + i;                            // this wavefront's row block
+      if (ib >= i0 && ib < i0 + 4) {
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = (ib - i0) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const int col = wn * 128 + jb * 32 + (lane & 31);
+            sC[row * DMA_CP + col] = acc[i][jb][r];
+          }
+      }
+    }
+    __syncthreads();
+    lds_epilogue<bf16, EPI, DMA_BN>(sC, DMA_CP, nb * 32, m0 + i0 * 32, n0, z, p);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Register-staged bf16 kernel (any K % 8 == 0).  4 wavefronts as 2x2, each owning a
+// 64x64 block = 2x2 MFMA tiles.  LDS rows are padded by 16 bytes so that the 16-byte
+// operand reads of 8 consecutive lanes fall into 8 different bank groups.
 // Operand layout of v_mfma_f32_32x32x16_bf16: lane l supplies row (l % 32) and the
 // 8 consecutive k values starting at 8 * (l / 32); the result lane l holds column
 // (l % 32), rows 8*(i/4) + 4*(l/32) + i%4 for i = 0..15.
@@ -221,7 +482,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
         sC[row * CPITCH16 + col] = acc[i][j][r];
       }
   __syncthreads();
-  epilogue<bf16, EPI, BM16, BN16>(sC, CPITCH16, m0, n0, p);
+  lds_epilogue<bf16, EPI, BN16>(sC, CPITCH16, BM16, m0, n0, blockIdx.z, p);
 }
 
 // ---------------------------------------------------------------------------
@@ -274,68 +535,100 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
     *reinterpret_cast<float4 *>(sC + (ty * 4 + i) * CPITCH32 + tx * 4) =
         make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
   __syncthreads();
-  epilogue<float, EPI, BM32, BN32>(sC, CPITCH32, m0, n0, p);
+  lds_epilogue<float, EPI, BN32>(sC, CPITCH32, BM32, m0, n0, blockIdx.z, p);
 }
 
-// out[r, c] = sum_z partial[z, r, c] (+ resid[resid_rows[r], c]), z ascending
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int splits,
-                                                            int M, int N, const float *__restrict__ resid,
-                                                            const int32_t *__restrict__ resid_rows,
-                                                            float *__restrict__ out) {
+// Adds the K-split partial sums in ascending split order and applies the epilogue.
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p) {
   const size_t i4 = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t total4 = (size_t)M * N / 4;
+  const size_t total4 = (size_t)p.M * p.N / 4;
   if (i4 >= total4) return;
   const size_t e = i4 * 4;
-  const int r = (int)(e / N), c = (int)(e % N);
+  const int r = (int)(e / p.N), c = (int)(e % p.N);
   float4 acc = make_float4(0, 0, 0, 0);
-  for (int z = 0; z < splits; ++z) {
-    const float4 v = *reinterpret_cast<const float4 *>(partial + (size_t)z * M * N + e);
+  for (int z = 0; z < p.splits; ++z) {
+    const float4 v = *reinterpret_cast<const float4 *>(p.partial + (size_t)z * p.M * p.N + e);
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
-  if (resid) {
-    const int rr = resid_rows ? resid_rows[r] : r;
-    const float4 q = *reinterpret_cast<const float4 *>(resid + (size_t)rr * N + c);
-    acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
-  }
-  *reinterpret_cast<float4 *>(out + e) = acc;
+  apply_epilogue<T, EPI>(acc, acc, r, c, p);
 }
 
 // ---------------------------------------------------------------------------
-static void tile_shape(int dtype, int epi, int *bm, int *out_cols, int *bk) {
-  if (dtype == 0) { *bm = BM32; *out_cols = epi == EPI_SWIGLU ? BN32 / 2 : BN32; *bk = BK32; }
-  else            { *bm = BM16; *out_cols = epi == EPI_SWIGLU ? BN16 / 2 : BN16; *bk = BK16; }
-}
+// Host side: choice of kernel, tile height and K split; launches.
+// ---------------------------------------------------------------------------
+struct GemmPlan {
+  int kind;        // 0 float, 1 register-staged bf16, 2 direct-to-LDS bf16
+  int I;           // kind 2: row blocks per tile
+  int bm, out_cols, bk;
+  int tiles_m, tiles_n, splits, k_per_split;
+};
 
-int gemm_splits(int dtype, int M, int N, int K) {
-  int bm, oc, bk;
-  tile_shape(dtype, EPI_F32, &bm, &oc, &bk);
-  const long tiles = (long)ceil_div(M, bm) * ceil_div(N, oc);
-  int want = (int)((512 + tiles - 1) / tiles);
-  int max_by_k = K / (4 * bk);             // at least 4 k-tiles per split
-  int s = want < 1 ? 1 : want;
-  if (s > 8) s = 8;
-  if (s > max_by_k) s = max_by_k < 1 ? 1 : max_by_k;
-  int kper = ceil_div(ceil_div(K, s), bk) * bk;
-  return ceil_div(K, kper);
-}
-
-template <int EPI>
-static void launch_typed(int dtype, dim3 grid, const GemmParams &p, hipStream_t s) {
-  if (dtype == 0) {
-    hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, s, p);
-  } else {
-    static bool attr_set = false;
-    if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<EPI>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBf16);
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), kSmemBf16, s, p);
+static int pick_row_blocks(int M) {
+  // padded rows divided by a rough efficiency of the tile height
+  const int cand[4] = {8, 6, 4, 2};
+  const double eff[4] = {1.0, 0.97, 0.88, 0.62};
+  int best = 8;
+  double best_cost = 1e30;
+  for (int i = 0; i < 4; ++i) {
+    const int bm = 32 * cand[i];
+    const double cost = (double)ceil_div(M, bm) * bm / eff[i];
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = cand[i]; }
   }
+  return best;
 }
 
-// Fills the kernel parameters and the launch grid for a problem.
-static void plan_gemm(const GemmArgs &g, GemmParams *pp, dim3 *grid) {
+static int pick_splits(long tiles, int k_tiles, int min_k_tiles) {
+  // smallest split count that fills >= 90 % of a whole number of 256-workgroup rounds
+  int best = 1;
+  double best_eff = 0;
+  for (int s = 1; s <= 16; ++s) {
+    if (s > 1 && k_tiles / s < min_k_tiles) break;
+    const long wgs = tiles * s;
+    const double eff = (double)wgs / (double)(ceil_div((int)wgs, 256) * 256L);
+    if (eff > best_eff + 1e-9) { best_eff = eff; best = s; }
+    if (eff >= 0.9) break;
+  }
+  return best;
+}
+
+static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
+  GemmPlan pl = {};
+  if (dtype == 0) {
+    pl.kind = 0; pl.bm = BM32; pl.out_cols = epi == EPI_SWIGLU ? BN32 / 2 : BN32; pl.bk = BK32;
+  } else if (K % DMA_BK == 0 && (epi == EPI_SWIGLU || (epi == EPI_F32 && K >= 8192))) {
+    // measured: the big-tile kernel wins where N or K is large (gate/up, down projection);
+    // the register-staged kernel with its finer tiles wins on the Q/K/V and output projections
+    pl.kind = 2; pl.I = pick_row_blocks(M); pl.bm = 32 * pl.I;
+    pl.out_cols = epi == EPI_SWIGLU ? DMA_BN / 2 : DMA_BN; pl.bk = DMA_BK;
+  } else {
+    pl.kind = 1; pl.bm = BM16; pl.out_cols = epi == EPI_SWIGLU ? BN16 / 2 : BN16; pl.bk = BK16;
+  }
+  pl.tiles_m = ceil_div(M, pl.bm);
+  pl.tiles_n = ceil_div(N, pl.out_cols);
+  pl.splits = 1;
+  const int k_tiles = ceil_div(K, pl.bk);
+  if (epi != EPI_SWIGLU)
+    pl.splits = pick_splits((long)pl.tiles_m * pl.tiles_n, k_tiles, pl.kind == 2 ? 8 : 4);
+  pl.k_per_split = ceil_div(k_tiles, pl.splits) * pl.bk;
+  pl.splits = ceil_div(K, pl.k_per_split);
+  return pl;
+}
+
+static int problem_n(const GemmArgs &g) {
+  if (g.epi == EPI_SWIGLU) return g.seg[0].n;
+  int n = 0;
+  for (int i = 0; i < (g.epi == EPI_SEG ? g.n_seg : 1); ++i) n += g.seg[i].n;
+  return n;
+}
+
+size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K) {
+  if (M <= 0) return 0;
+  const GemmPlan pl = make_plan(dtype, epi, M, N, K);
+  return pl.splits > 1 ? (size_t)pl.splits * M * N : 0;
+}
+
+static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   GemmParams &p = *pp;
   p = GemmParams{};
   p.a = g.a; p.lda = g.lda; p.a_rows = g.a_rows; p.M = g.M; p.K = g.K;
@@ -346,50 +639,87 @@ static void plan_gemm(const GemmArgs &g, GemmParams *pp, dim3 *grid) {
     p.row_map[i] = g.seg[i].row_map; p.rope[i] = g.seg[i].rope;
     p.nb[i + 1] = p.nb[i] + (i < p.n_seg ? g.seg[i].n : 0);
   }
-  p.N = g.epi == EPI_SWIGLU ? g.seg[0].n : p.nb[p.n_seg];
+  p.N = problem_n(g);
   p.rope_tab = g.rope_tab; p.row_pos = g.row_pos; p.head_dim = g.head_dim;
   p.out_f32 = g.out_f32; p.resid = g.resid; p.resid_rows = g.resid_rows; p.partial = g.partial;
-  int bm, oc, bk;
-  tile_shape(g.dtype, g.epi, &bm, &oc, &bk);
-  p.splits = 1;
-  p.k_per_split = ceil_div(g.K, bk) * bk;
-  if (g.epi == EPI_F32) {
-    p.splits = gemm_splits(g.dtype, g.M, p.N, g.K);
-    if (p.splits > 1) {
-      if (!g.partial || g.partial_floats < (size_t)p.splits * g.M * p.N) p.splits = 1;
-      else p.k_per_split = ceil_div(ceil_div(g.K, p.splits), bk) * bk;
-    }
+  GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K);
+  if (pl.splits > 1 && (!g.partial || g.partial_floats < (size_t)pl.splits * g.M * p.N)) {
+    pl.splits = 1;                                   // no scratch: one pass over K
+    pl.k_per_split = ceil_div(g.K, pl.bk) * pl.bk;
   }
-  *grid = dim3(ceil_div(p.N, oc), ceil_div(g.M, bm), p.splits);
+  p.splits = pl.splits;
+  p.k_per_split = pl.k_per_split;
+  return pl;
 }
 
 bool gemm_needs_reduce(const GemmArgs &g) {
-  if (g.M == 0 || g.epi != EPI_F32) return false;
+  if (g.M == 0) return false;
   GemmParams p;
-  dim3 grid;
-  plan_gemm(g, &p, &grid);
-  return p.splits > 1;
+  return fill_params(g, &p).splits > 1;
+}
+
+template <int I, int EPI>
+static void launch_dma(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
+  constexpr int smem = dma_smem_bytes(I);
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<I, EPI>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_set = true;
+  }
+  const int nblk = ceil_div(pl.tiles_n, 8);
+  const unsigned grid = 8u * nblk * pl.tiles_m * pl.splits;
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, EPI>), dim3(grid), dim3(256), smem, s, p, pl.tiles_m,
+                     pl.tiles_n);
+}
+
+template <int EPI>
+static void launch_typed(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
+  const dim3 grid(pl.tiles_n, pl.tiles_m, pl.splits);
+  if (pl.kind == 0) {
+    hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, s, p);
+  } else if (pl.kind == 1) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<EPI>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBf16);
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), kSmemBf16, s, p);
+  } else {
+    switch (pl.I) {
+      case 2: launch_dma<2, EPI>(pl, p, s); break;
+      case 4: launch_dma<4, EPI>(pl, p, s); break;
+      case 6: launch_dma<6, EPI>(pl, p, s); break;
+      default: launch_dma<8, EPI>(pl, p, s); break;
+    }
+  }
 }
 
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s) {
   if (g.M == 0) return hipSuccess;
   GemmParams p;
-  dim3 grid;
-  plan_gemm(g, &p, &grid);
-  if (g.epi == EPI_SEG) launch_typed<EPI_SEG>(g.dtype, grid, p, s);
-  else if (g.epi == EPI_SWIGLU) launch_typed<EPI_SWIGLU>(g.dtype, grid, p, s);
-  else launch_typed<EPI_F32>(g.dtype, grid, p, s);
+  const GemmPlan pl = fill_params(g, &p);
+  if (g.epi == EPI_SEG) launch_typed<EPI_SEG>(pl, p, s);
+  else if (g.epi == EPI_SWIGLU) launch_typed<EPI_SWIGLU>(pl, p, s);
+  else launch_typed<EPI_F32>(pl, p, s);
   return hipGetLastError();
 }
 
 hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
-  if (!gemm_needs_reduce(g)) return hipSuccess;
+  if (g.M == 0) return hipSuccess;
   GemmParams p;
-  dim3 grid;
-  plan_gemm(g, &p, &grid);
-  size_t total4 = (size_t)g.M * p.N / 4;
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total4 + 255) / 256)), dim3(256), 0, s,
-                     g.partial, p.splits, g.M, p.N, g.resid, g.resid_rows, g.out_f32);
+  const GemmPlan pl = fill_params(g, &p);
+  if (pl.splits <= 1) return hipSuccess;
+  const size_t total4 = (size_t)g.M * p.N / 4;
+  const dim3 grid((unsigned)((total4 + 255) / 256));
+  if (g.dtype == 0) {
+    if (g.epi == EPI_SEG) hipLaunchKernelGGL((splitk_reduce_kernel<float, EPI_SEG>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<float, EPI_F32>), grid, dim3(256), 0, s, p);
+  } else {
+    if (g.epi == EPI_SEG) hipLaunchKernelGGL((splitk_reduce_kernel<bf16, EPI_SEG>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<bf16, EPI_F32>), grid, dim3(256), 0, s, p);
+  }
   return hipGetLastError();
 }
 

@@ -63,13 +63,14 @@ struct GemmArgs {
   float *out_f32;          // EPI_F32: [M, n] float output, pitch n
   const float *resid;      // EPI_F32: added to the output; row r reads resid[resid_rows[r]]
   const int32_t *resid_rows;
-  float *partial;          // EPI_F32: split-K scratch, >= splits*M*n floats when splits > 1
+  float *partial;          // split-K scratch (gemm_partial_floats); too small or NULL: no split
   size_t partial_floats;
 };
-// Number of K splits launch_gemm will use for an EPI_F32 problem (for workspace sizing).
-int gemm_splits(int dtype, int M, int N, int K);
-// Main kernel.  An EPI_F32 problem that was split along K (gemm_needs_reduce) leaves partial
-// sums in g.partial and must be completed by launch_gemm_reduce on the same stream.
+// Floats of split-K scratch a problem of this shape uses (0 when it is not split); N is the
+// total number of output columns (d_ff for EPI_SWIGLU).  For workspace sizing.
+size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K);
+// Main kernel.  A problem that was split along K (gemm_needs_reduce) leaves raw partial sums
+// in g.partial and must be completed by launch_gemm_reduce on the same stream.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
 bool gemm_needs_reduce(const GemmArgs &g);
 hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s);
