@@ -91,6 +91,9 @@ size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim + 2 * kv_dim, d));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, q_dim));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, m.d_ff));
+    // the attention KV split borrows the same scratch (the two are never live together)
+    need = std::max(need, attention_partial_floats(m.dtype, mm, m.n_q_heads, m.n_kv_heads, m.head_dim,
+                                                   c->max_tokens));
     if (mm == max_rows) break;
   }
   return need;
@@ -148,7 +151,7 @@ int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int 
 
 // the layer body; arguments already validated
 int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, const int32_t *row_pos,
-                    int n, int S, void *kc, void *vc, int k, const int32_t *forced, float *h_out,
+                    int n, int S, void *kc, void *vc, int n_tokens, int k, const int32_t *forced, float *h_out,
                     int32_t *pos_out, float *dev_out, const LayerWs &ws, hipStream_t s) {
   const cb_model_desc &m = c->m;
   const int dt = m.dtype;
@@ -235,7 +238,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   {
     ProfScope ps(c, s, CB_PROF_ATTN, 0, 0);
     CB_HIP(launch_attention(dt, ws.qbuf, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads, m.n_kv_heads,
-                            m.head_dim, s));
+                            m.head_dim, n_tokens, ws.partial, ws.partial_floats, s));
   }
   // h = H + o Wo^T
   GemmArgs f = {};
@@ -409,7 +412,7 @@ int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const flo
   if (n_rows == 0) return CB_OK;
   LayerWs ws = carve_layer(c, (char *)workspace, n_rows);
   if (ws.bytes > workspace_bytes) return CB_EWORKSPACE;
-  return fuse_layer_impl(c, w, h_in, row_pos, n_rows, n_suffix, k_cache, v_cache, k_keep, forced_sel,
+  return fuse_layer_impl(c, w, h_in, row_pos, n_rows, n_suffix, k_cache, v_cache, n_tokens_total, k_keep, forced_sel,
                          h_out, pos_out, dev_out, ws, (hipStream_t)stream);
 }
 
@@ -465,7 +468,7 @@ int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, co
     const int32_t *forced = forced_sel ? forced_sel[l] : nullptr;
     float *dev_out = dev_dump ? dev_dump[l] : nullptr;
     st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, n, n_suffix, k_cache_layers[l], v_cache_layers[l],
-                         k, forced, h_nxt, p_nxt, dev_out, ws, s);
+                         T, k, forced, h_nxt, p_nxt, dev_out, ws, s);
     if (st != CB_OK) return st;
     if (sel_dump && sel_dump[l] && k > 0)
       CB_HIP(hipMemcpyAsync(sel_dump[l], p_nxt, (size_t)k * 4, hipMemcpyDeviceToDevice, s));

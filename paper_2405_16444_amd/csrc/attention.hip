@@ -18,6 +18,7 @@
 // float kernel: one wavefront per (row, query head), 64 keys per step, plain FMA.
 #include "common.h"
 #include "kernels.h"
+#include <algorithm>
 
 namespace cb {
 
@@ -33,7 +34,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
                                                         const int32_t *__restrict__ q_pos, int n_rows,
                                                         const bf16 *__restrict__ kc,
                                                         const bf16 *__restrict__ vc, bf16 *__restrict__ o,
-                                                        int n_q_heads, int n_kv_heads, float scale_log2e) {
+                                                        int n_q_heads, int n_kv_heads, float scale_log2e,
+                                                        int split_tiles, float *__restrict__ part_o,
+                                                        float *__restrict__ part_ml) {
   constexpr int KP = DH + 8;            // K tile pitch (elements)
   constexpr int KS = DH / 16;           // k-steps of the first product
   constexpr int DB = DH / 32;           // 32-channel blocks of the output
@@ -55,7 +58,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
   // causal bound of the workgroup = position of its last valid row
   const int last_m = min(m_wg + 128 * NQB, n_flat) - 1;
   const int kv_len = q_pos[last_m / g] + 1;
-  const int n_tiles = (kv_len + BKV - 1) / BKV;
+  const int n_tiles_all = (kv_len + BKV - 1) / BKV;
+  // KV split: workgroup z of gridDim.z handles tiles [t_begin, n_tiles) of the causal range and
+  // leaves un-normalised partial results (flash-decoding style) for the merge kernel
+  const int t_begin = blockIdx.z * split_tiles;
+  if (t_begin >= n_tiles_all) return;
+  const int n_tiles = min(n_tiles_all, t_begin + split_tiles);
 
   // this lane's queries
   int my_pos[NQB];
@@ -124,12 +132,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
     }
   };
 
-  if (n_tiles > 0) {
-    gload(0);
-    sstore(0);
-  }
+  gload(t_begin * BKV);
+  sstore(t_begin & 1);
   __syncthreads();
-  for (int t = 0; t < n_tiles; ++t) {
+  for (int t = t_begin; t < n_tiles; ++t) {
     const int t0 = t * BKV;
     if (t + 1 < n_tiles) gload(t0 + BKV);
     if (t0 <= wave_max_pos) {  // wave-uniform: tiles wholly in this wave's future are skipped
@@ -204,6 +210,29 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
     if (t + 1 < n_tiles) sstore((t + 1) & 1);
     __syncthreads();
   }
+  if (gridDim.z > 1) {
+    // ---- partial results: O (un-normalised), running max and sum per (kv head, query, split) ----
+#pragma unroll
+    for (int b = 0; b < NQB; ++b) {
+      const float tot = row_sum[b] + __shfl_xor(row_sum[b], 32, 64);
+      if (!valid[b]) continue;
+      const int m = m_wg + (wave * NQB + b) * 32 + ln;
+      const size_t slot = ((size_t)kvh * n_flat + m) * gridDim.z + blockIdx.z;
+      if (h == 0) {
+        part_ml[slot * 2] = row_max[b];
+        part_ml[slot * 2 + 1] = tot;
+      }
+      float *dst = part_o + slot * DH;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+          *reinterpret_cast<float4 *>(dst + d * 32 + a * 8 + h * 4) =
+              make_float4(oacc[b][d][a * 4 + 0], oacc[b][d][a * 4 + 1], oacc[b][d][a * 4 + 2],
+                          oacc[b][d][a * 4 + 3]);
+    }
+    return;
+  }
   // ---- normalise and store ----
 #pragma unroll
   for (int b = 0; b < NQB; ++b) {
@@ -220,6 +249,42 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
         *reinterpret_cast<bf16x4 *>(dst + d * 32 + a * 8 + h * 4) = w;
       }
   }
+}
+
+// Merge of the KV-split partials: o = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s over the
+// splits that ran for the query's workgroup (those below its causal bound).
+template <int DH>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict__ part_o,
+                                                         const float *__restrict__ part_ml,
+                                                         const int32_t *__restrict__ q_pos, int n_rows,
+                                                         bf16 *__restrict__ o, int n_q_heads,
+                                                         int n_kv_heads, int n_splits, int split_tiles,
+                                                         int wg_queries) {
+  constexpr int CG = DH / 4;                           // float4 channel groups per query
+  const int g = n_q_heads / n_kv_heads, n_flat = n_rows * g;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)n_kv_heads * n_flat * CG) return;
+  const int c = (int)(idx % CG);
+  const long qh = idx / CG;                            // kvh * n_flat + m
+  const int m = (int)(qh % n_flat), kvh = (int)(qh / n_flat);
+  const int last_m = min((m / wg_queries + 1) * wg_queries, n_flat) - 1;
+  const int n_tiles = (q_pos[last_m / g] + BKV) / BKV;
+  const int ns = min(n_splits, (n_tiles + split_tiles - 1) / split_tiles);
+  const float *ml = part_ml + qh * n_splits * 2;
+  float mx = kNegBig;
+  for (int s = 0; s < ns; ++s) mx = fmaxf(mx, ml[2 * s]);
+  float den = 0.f;
+  float4 acc = make_float4(0, 0, 0, 0);
+  for (int s = 0; s < ns; ++s) {
+    const float w = exp2f(ml[2 * s] - mx);
+    den += w * ml[2 * s + 1];
+    const float4 v = *reinterpret_cast<const float4 *>(part_o + (qh * n_splits + s) * DH + c * 4);
+    acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+  }
+  const float inv = 1.f / den;
+  const int r = m / g, j = m - r * g;
+  bf16x4 w4 = {(bf16)(acc.x * inv), (bf16)(acc.y * inv), (bf16)(acc.z * inv), (bf16)(acc.w * inv)};
+  *reinterpret_cast<bf16x4 *>(o + ((size_t)r * n_q_heads + kvh * g + j) * DH + c * 4) = w4;
 }
 
 // ---------------------------------------------------------------------------
@@ -279,9 +344,36 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
     if (lane + 64 * c < DH) orow[lane + 64 * c] = acc[c] / run_sum;
 }
 
+// Split plan of the bf16 kernel: few query workgroups (the selective layers) leave most CUs
+// idle, so the key range is cut into n_splits pieces handled by separate workgroups.
+static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *nqb, int *n_splits,
+                            int *split_tiles) {
+  const long n_flat = (long)n_rows * (hq / hkv);
+  const bool big = ((n_flat + 255) / 256) * hkv >= 512;
+  *nqb = big ? 2 : 1;
+  const long base = ((n_flat + 128 * *nqb - 1) / (128 * *nqb)) * hkv;
+  const int max_tiles = (n_tokens + BKV - 1) / BKV;
+  int ns = 1;
+  if (base < 384) {
+    ns = (int)((768 + base - 1) / base);
+    ns = std::min(ns, std::max(1, max_tiles / 4));
+    ns = std::min(ns, 32);
+  }
+  *split_tiles = (max_tiles + ns - 1) / ns;
+  *n_splits = (max_tiles + *split_tiles - 1) / *split_tiles;
+}
+
+size_t attention_partial_floats(int dtype, int n_rows, int hq, int hkv, int dh, int n_tokens) {
+  if (dtype == 0 || n_rows == 0) return 0;
+  int nqb, ns, st;
+  attn_split_plan(n_rows, hq, hkv, n_tokens, &nqb, &ns, &st);
+  if (ns <= 1) return 0;
+  return (size_t)n_rows * hq * ns * (dh + 2);
+}
+
 hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int n_rows,
                             const void *kc, const void *vc, void *o, int hq, int hkv, int dh,
-                            hipStream_t s) {
+                            int n_tokens, float *partial, size_t partial_floats, hipStream_t s) {
   if (n_rows == 0) return hipSuccess;
   const float scale_log2e = kLog2e / sqrtf((float)dh);
   if (dtype == 0) {
@@ -296,8 +388,14 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int 
   }
   const int g = hq / hkv;
   const long n_flat = (long)n_rows * g;
-  // two query blocks per wavefront once that still yields enough workgroups
-  const bool big = ((n_flat + 255) / 256) * hkv >= 512;
+  int nqb, n_splits, split_tiles;
+  attn_split_plan(n_rows, hq, hkv, n_tokens, &nqb, &n_splits, &split_tiles);
+  if (n_splits > 1 && (!partial || partial_floats < (size_t)n_rows * hq * n_splits * (dh + 2))) {
+    n_splits = 1;                                    // no scratch: one workgroup walks all keys
+    split_tiles = (n_tokens + BKV - 1) / BKV;
+  }
+  float *part_o = partial;
+  float *part_ml = partial ? partial + (size_t)n_rows * hq * n_splits * dh : nullptr;
 #define CB_ATTN(DH_, NQB_)                                                                          \
   do {                                                                                              \
     constexpr int smem = 2 * (BKV * (DH_ + 8) + DH_ * VT_PITCH) * 2;                                \
@@ -308,13 +406,24 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int 
       attr_set = true;                                                                              \
     }                                                                                               \
     hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_>),                                               \
-                       dim3((unsigned)((n_flat + 128 * NQB_ - 1) / (128 * NQB_)), hkv), dim3(256),  \
-                       smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc, (const bf16 *)vc, \
-                       (bf16 *)o, hq, hkv, scale_log2e);                                            \
+                       dim3((unsigned)((n_flat + 128 * NQB_ - 1) / (128 * NQB_)), hkv, n_splits),   \
+                       dim3(256), smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc,        \
+                       (const bf16 *)vc, (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o,      \
+                       part_ml);                                                                    \
   } while (0)
-  if (dh == 64) { if (big) CB_ATTN(64, 2); else CB_ATTN(64, 1); }
-  else          { if (big) CB_ATTN(128, 2); else CB_ATTN(128, 1); }
+  if (dh == 64) { if (nqb == 2) CB_ATTN(64, 2); else CB_ATTN(64, 1); }
+  else          { if (nqb == 2) CB_ATTN(128, 2); else CB_ATTN(128, 1); }
 #undef CB_ATTN
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || n_splits == 1) return e;
+  const long total = (long)hkv * n_flat * (dh / 4);
+  const dim3 mgrid((unsigned)((total + 255) / 256));
+  if (dh == 64)
+    hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, 128 * nqb);
+  else
+    hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, 128 * nqb);
   return hipGetLastError();
 }
 
