@@ -1,0 +1,119 @@
+"""Parity at the real widths of the benchmark workloads, in the launch configurations
+bench.py times (row counts of the gradual schedule, 3136 / 4064 / 32896-token caches).
+Inputs are synthetic single-layer cases from the seeded generator (random cache rows, random
+hidden rows): a full-width end-to-end oracle run would take minutes, a single layer takes
+seconds.  Where even one layer is too much for the oracle (the dense layer 0), the cache rows
+are checked in full and the layer output on sampled rows, which the oracle computes one by
+one from its own K/V."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cacheblend_oracle as O
+from workloads import synth
+from workloads.configs import WORKLOADS
+
+from gpu_util import TOL, announce, dev_layers, max_abs_rel, np_layers, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2405_16444_amd as pkg
+    return pkg
+
+
+_layer_cache = {}
+
+
+def full_layer(name):
+    """One layer of the named workload's model: (torch weights on cpu, float64 copies)."""
+    if name not in _layer_cache:
+        _layer_cache.clear()                     # one 200-850 M parameter layer at a time
+        w = WORKLOADS[name]
+        lw = synth.layer_weights(w.model, 1, w.seed_weights)
+        _layer_cache[name] = (lw, np_layers([lw])[0])
+    return _layer_cache[name]
+
+
+def case(model, n_tokens, n_rows, n_suffix, seed):
+    g = torch.Generator().manual_seed(seed)
+    dt = synth.storage_dtype(model)
+    h = synth.random_rows(n_rows, model.d_model, 1.0, seed + 1)
+    n_ctx = n_tokens - n_suffix
+    ctx_rows = torch.sort(torch.randperm(n_ctx, generator=g)[:n_rows - n_suffix]).values
+    pos = torch.cat([ctx_rows, torch.arange(n_ctx, n_tokens)]).to(torch.int32)
+    shape = (n_tokens, model.n_kv_heads, model.head_dim)
+    kc = synth.random_rows(n_tokens, model.kv_dim, 0.5, seed + 2, dtype=dt).view(shape)
+    vc = synth.random_rows(n_tokens, model.kv_dim, 0.5, seed + 3, dtype=dt).view(shape)
+    return h, pos, kc, vc
+
+
+def run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, want_dev):
+    ctx = P.cb_create(model, kc.shape[0])
+    dlw = dev_layers([lw])[0]
+    kg, vg = kc.cuda().contiguous(), vc.cuda().contiguous()
+    h_out, pos_out, dev = P.cb_fuse_layer(ctx, 0, dlw, h.cuda(), pos.cuda(), n_suffix, kg, vg, k_keep,
+                                          want_dev=want_dev)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    del dlw
+    return h_out.cpu(), pos_out.cpu(), None if dev is None else dev.cpu(), kg.cpu(), vg.cpu()
+
+
+@pytest.mark.parametrize("name,n_tokens,n_rows,n_suffix,k_keep", [
+    ("mistral7b", 3136, 986, 64, 877),        # layer 2 of the gradual schedule: check on 922 candidates
+    ("mistral7b", 3136, 359, 64, 231),        # last layer: 295 candidates -> 231
+    ("yi34b", 3136, 525, 64, 400),            # 7 query heads per kv head, d = 7168
+    ("llama70b", 4064, 300, 64, 200),         # 8 query heads per kv head, d = 8192, d_ff = 28672
+    ("long32k", 32896, 700, 128, 500),        # 32 K-token cache: attention KV split + long positions
+])
+def test_selective_layer_at_real_width(P, name, n_tokens, n_rows, n_suffix, k_keep):
+    w = WORKLOADS[name]
+    model = replace(w.model, n_layers=1)
+    announce("selective layer at real width", name, n_tokens, n_rows, n_suffix, k_keep)
+    lw, nlw = full_layer(name)
+    h, pos, kc, vc = case(model, n_tokens, n_rows, n_suffix, seed=7000 + n_rows)
+    h_out, pos_out, dev, kg, vg = run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, True)
+    tol = TOL["bf16"]
+    n_cand = n_rows - n_suffix
+    sel_pos = pos.numpy()[:n_cand][O.top_k_indices(dev.numpy(), k_keep)]
+    assert np.array_equal(pos_out.numpy()[:k_keep], sel_pos)                 # bit-exact selection
+    ko, vo = to_np(kc), to_np(vc)
+    h_ref, pos_ref, dev_ref, _ = O.fuse_layer(nlw, model, to_np(h), pos.numpy(), n_suffix, ko, vo, k_keep,
+                                              forced_sel=sel_pos, kv_round=O.round_bf16)
+    assert max_abs_rel(dev.numpy(), dev_ref) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    untouched = np.setdiff1d(np.arange(n_tokens), pos_ref)
+    assert torch.equal(kg[untouched], kc[untouched]) and torch.equal(vg[untouched], vc[untouched])
+    err = max_abs_rel(to_np(h_out), h_ref)
+    print(f"{name}: h_out max-abs-rel {err:.2e}")
+    assert err < tol
+
+
+def test_dense_first_layer_at_real_width_sampled(P):
+    """Layer 0 of the Mistral-7B-shaped workload: all 3136 rows, no check.  K/V rows are compared
+    in full; the layer output on 48 sampled rows."""
+    w = WORKLOADS["mistral7b"]
+    model = replace(w.model, n_layers=1)
+    T, S = w.n_tokens, w.n_suffix
+    announce("dense first layer, sampled", T)
+    lw, nlw = full_layer("mistral7b")
+    h, pos, kc, vc = case(model, T, T, S, seed=9100)
+    h_out, pos_out, _, kg, vg = run_gpu(P, model, lw, h, pos, kc, vc, S, T - S, False)
+    assert np.array_equal(pos_out.numpy(), np.arange(T))
+    hn = to_np(h)
+    xn, k_ref, v_ref = O.project_kv(hn, np.arange(T), nlw, model)
+    k_ref, v_ref = O.round_bf16(k_ref), O.round_bf16(v_ref)
+    tol = TOL["bf16"]
+    assert max_abs_rel(to_np(kg), k_ref) < tol and max_abs_rel(to_np(vg), v_ref) < tol
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, T - 1], np.random.default_rng(5).integers(0, T, 41)]))
+    q = O.project_q(xn[rows], rows, nlw, model)
+    o = O.attention(q, rows, k_ref, v_ref)
+    ref = O.finish_block(hn[rows], o, nlw, model)
+    err = max_abs_rel(to_np(h_out)[rows], ref)
+    print(f"dense layer 0: sampled h_out max-abs-rel {err:.2e}")
+    assert err < tol
