@@ -19,6 +19,7 @@
 #include "common.h"
 #include "kernels.h"
 #include <algorithm>
+#include <cstdlib>
 
 namespace cb {
 
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
   long q_off[NQB];
   bool valid[NQB];
   bf16x8 qf[NQB][KS];
-  int wave_max_pos = -1;
+  int wave_max_pos = -1, wave_min_pos = 0x7fffffff;
 #pragma unroll
   for (int b = 0; b < NQB; ++b) {
     const int m = m_wg + (wave * NQB + b) * 32 + ln;
@@ -83,8 +84,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
     for (int ks = 0; ks < KS; ++ks)
       qf[b][ks] = *reinterpret_cast<const bf16x8 *>(q + q_off[b] + ks * 16 + 8 * h);
     wave_max_pos = max(wave_max_pos, my_pos[b]);
+    wave_min_pos = min(wave_min_pos, my_pos[b]);       // invalid queries (-1) force masking
   }
   wave_max_pos = (int)wave_max((float)wave_max_pos);  // positions < 2^24: exact in float
+  wave_min_pos = -(int)wave_max((float)(-wave_min_pos));
 
   f32x16 oacc[NQB][DB];
   float row_max[NQB], row_sum[NQB];
@@ -159,38 +162,49 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
             sacc[b][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], sacc[b][kb], 0, 0, 0);
         }
       }
-      // ---- online softmax (per lane = per query) ----
+      // ---- online softmax (per lane = per query), in the raw score domain: p = 2^((s - m) c) ----
       bf16x8 pf[NQB][4];
+      const bool diag = t0 + BKV - 1 > wave_min_pos;     // wave-uniform: some key of the tile is masked
 #pragma unroll
       for (int b = 0; b < NQB; ++b) {
         float mx = kNegBig;
+        if (diag) {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = t0 + kb * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
+              sacc[b][kb][i] = key <= my_pos[b] ? sacc[b][kb][i] : kNegBig;
+            }
+        }
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = t0 + kb * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
-            float s = key <= my_pos[b] ? sacc[b][kb][i] * scale_log2e : kNegBig;
-            sacc[b][kb][i] = s;
-            mx = fmaxf(mx, s);
-          }
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[b][kb][i]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float new_max = fmaxf(row_max[b], mx);
-        const float alpha = exp2f(row_max[b] - new_max);
-        row_max[b] = new_max;
+        const float neg_mc = -new_max * scale_log2e;
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            const float pv = exp2f(sacc[b][kb][i] - new_max);
+            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[b][kb][i], scale_log2e, neg_mc));
             psum += pv;
             pf[b][kb * 2 + (i >> 3)][i & 7] = (bf16)pv;
           }
-        row_sum[b] = row_sum[b] * alpha + psum;
+        // the accumulators only need rescaling when some query's running max moved, which
+        // becomes rare after the first tiles
+        if (__any(new_max > row_max[b])) {
+          const float alpha = __builtin_amdgcn_exp2f((row_max[b] - new_max) * scale_log2e);
+          row_sum[b] *= alpha;
 #pragma unroll
-        for (int d = 0; d < DB; ++d)
+          for (int d = 0; d < DB; ++d)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[b][d][i] *= alpha;
+            for (int i = 0; i < 16; ++i) oacc[b][d][i] *= alpha;
+          row_max[b] = new_max;
+        }
+        row_sum[b] += psum;
       }
       // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -219,7 +233,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
       const int m = m_wg + (wave * NQB + b) * 32 + ln;
       const size_t slot = ((size_t)kvh * n_flat + m) * gridDim.z + blockIdx.z;
       if (h == 0) {
-        part_ml[slot * 2] = row_max[b];
+        part_ml[slot * 2] = row_max[b] * scale_log2e;
         part_ml[slot * 2 + 1] = tot;
       }
       float *dst = part_o + slot * DH;
@@ -349,7 +363,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *nqb, int *n_splits,
                             int *split_tiles) {
   const long n_flat = (long)n_rows * (hq / hkv);
-  const bool big = ((n_flat + 255) / 256) * hkv >= 512;
+  const bool big = ((n_flat + 255) / 256) * hkv >= 512 && !getenv("CB_NQB1");
   *nqb = big ? 2 : 1;
   const long base = ((n_flat + 128 * *nqb - 1) / (128 * *nqb)) * hkv;
   const int max_tiles = (n_tokens + BKV - 1) / BKV;

@@ -57,15 +57,31 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float *__restri
         if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
       }
       __syncthreads();
-      if (tid == 0) {
-        unsigned cum = 0, digit = 0, nd = need;
-        for (int d = 255; d >= 0; --d) {
-          unsigned h = hist[d];
-          if (cum + h >= need) { digit = (unsigned)d; nd = need - cum; break; }
-          cum += h;
+      if (tid < 64) {
+        // digits are scanned from 255 downwards by one wavefront: lane l owns digits
+        // 255-4l .. 252-4l; a wavefront prefix sum finds the lane, then the digit, at which
+        // the running count reaches `need`
+        unsigned hcnt[4], local = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { hcnt[q] = hist[255 - 4 * tid - q]; local += hcnt[q]; }
+        unsigned incl = local;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          unsigned v = __shfl_up(incl, o, 64);
+          if (tid >= o) incl += v;
         }
-        s_prefix = prefix | (digit << shift);
-        s_need = nd;
+        const unsigned long long hit = __ballot(incl >= need);
+        const int first = __ffsll((long long)hit) - 1;        // lowest lane whose inclusive sum reaches need
+        if (tid == first) {
+          unsigned cum = incl - local, digit = 0, nd = need;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (cum + hcnt[q] >= need) { digit = 255u - 4u * tid - q; nd = need - cum; break; }
+            cum += hcnt[q];
+          }
+          s_prefix = prefix | (digit << shift);
+          s_need = nd;
+        }
       }
       __syncthreads();
       prefix = s_prefix;
