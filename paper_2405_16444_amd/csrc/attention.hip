@@ -19,7 +19,6 @@
 #include "common.h"
 #include "kernels.h"
 #include <algorithm>
-#include <cstdlib>
 
 namespace cb {
 
@@ -363,7 +362,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *nqb, int *n_splits,
                             int *split_tiles) {
   const long n_flat = (long)n_rows * (hq / hkv);
-  const bool big = ((n_flat + 255) / 256) * hkv >= 512 && !getenv("CB_NQB1");
+  const bool big = ((n_flat + 255) / 256) * hkv >= 512;
   *nqb = big ? 2 : 1;
   const long base = ((n_flat + 128 * *nqb - 1) / (128 * *nqb)) * hkv;
   const int max_tiles = (n_tokens + BKV - 1) / BKV;

@@ -232,7 +232,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   for (int i = 0; i < LW; ++i) {
     const int r = (wave + 4 * i) * 8 + (lane >> 3);           // row of the weight tile
     const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
-    src_w[i] = weight_row<bf16, EPI>(p, n0 + r, DMA_BN / 2, n0, r) + chunk * 8 + kb;
+    const bf16 *wrow;
+    if (EPI == EPI_SWIGLU) {
+      // each wavefront column block of 128 tile columns holds 64 gate columns followed by the
+      // SAME 64 up columns, so that a lane ends up with gate and up of one output element
+      const int which = (r >> 6) & 1, oc = min(n0 + (r >> 7) * 64 + (r & 63), p.N - 1);
+      wrow = reinterpret_cast<const bf16 *>(p.w[which]) + (size_t)oc * p.K;
+    } else {
+      wrow = weight_row<bf16, EPI>(p, n0 + r, DMA_BN / 2, n0, r);
+    }
+    src_w[i] = wrow + chunk * 8 + kb;
   }
   // load number idx of tile t: idx < LA activation, else weight; tile indices are clamped so
   // that every tile issues the same number of loads
@@ -348,7 +357,51 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     step(0, true, nk - 1, 3, false, 0);
     step(1, false, 0, 0, false, 0);
   }
-  // drain the clamped tail loads before the ring is reused as the parking area
+  if (EPI != EPI_SEG) {
+    // Epilogue straight from the accumulator registers: lane l holds column (l % 32) of each of
+    // its four 32-column blocks and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row block.
+    const int h = lane >> 5, ln = lane & 31;
+#pragma unroll
+    for (int i = 0; i < IH; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int gr = m0 + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+        if (gr >= p.M) continue;
+        if (EPI == EPI_SWIGLU) {
+          bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
+#pragma unroll
+          for (int jb = 0; jb < 2; ++jb) {
+            const int gc = n0 + wn * 64 + jb * 32 + ln;
+            if (gc >= p.N) continue;
+            const float gt = acc[i][jb][r], up = acc[i][jb + 2][r];
+            // silu(g) * u = g * u / (1 + 2^(-g log2 e))
+            const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt);
+            orow[gc] = (bf16)(gt * up * __builtin_amdgcn_rcpf(den));
+          }
+        } else {
+          if (p.splits > 1) {
+            float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+              const int gc = n0 + wn * 128 + jb * 32 + ln;
+              if (gc < p.N) prow[gc] = acc[i][jb][r];
+            }
+          } else {
+            const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
+            const float *res = p.resid ? p.resid + (size_t)rr * p.N : nullptr;
+            float *orow = p.out_f32 + (size_t)gr * p.N;
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+              const int gc = n0 + wn * 128 + jb * 32 + ln;
+              if (gc < p.N) orow[gc] = acc[i][jb][r] + (res ? res[gc] : 0.f);
+            }
+          }
+        }
+      }
+    }
+    return;
+  }
+  // EPI_SEG: drain the clamped tail loads, then reuse the rings as the parking area
   vm_wait<0>();
   __syncthreads();
   float *sC = reinterpret_cast<float *>(smem);
@@ -578,16 +631,18 @@ static int pick_row_blocks(int M) {
   return best;
 }
 
-static int pick_splits(long tiles, int k_tiles, int min_k_tiles) {
-  // smallest split count that fills >= 90 % of a whole number of 256-workgroup rounds
+// K-split count from a small cost model (microseconds): rounds of 256 workgroups, each walking
+// k_tiles / s tiles of t_tile us, plus the traffic of the partial sums (written and read back
+// once per split at ~4 TB/s) when s > 1.  t_tile comes from measurements of the two kernels.
+static int pick_splits(long tiles, int k_tiles, int min_k_tiles, double t_tile, double mn) {
   int best = 1;
-  double best_eff = 0;
+  double best_cost = 1e30;
+  const double reduce_us = mn * 8.0 / 4.0e6;           // bytes / (4 TB/s) in us, per split
   for (int s = 1; s <= 16; ++s) {
     if (s > 1 && k_tiles / s < min_k_tiles) break;
-    const long wgs = tiles * s;
-    const double eff = (double)wgs / (double)(ceil_div((int)wgs, 256) * 256L);
-    if (eff > best_eff + 1e-9) { best_eff = eff; best = s; }
-    if (eff >= 0.9) break;
+    const double rounds = (double)((tiles * s + 255) / 256);
+    const double cost = rounds * ((k_tiles + s - 1) / s) * t_tile + (s > 1 ? s * reduce_us + 6.0 : 0.0);
+    if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
   }
   return best;
 }
@@ -608,8 +663,23 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   pl.tiles_n = ceil_div(N, pl.out_cols);
   pl.splits = 1;
   const int k_tiles = ceil_div(K, pl.bk);
-  if (epi != EPI_SWIGLU)
-    pl.splits = pick_splits((long)pl.tiles_m * pl.tiles_n, k_tiles, pl.kind == 2 ? 8 : 4);
+  const long tiles = (long)pl.tiles_m * pl.tiles_n;
+  if (epi != EPI_SWIGLU) {
+    if (pl.kind == 2) {
+      pl.splits = pick_splits(tiles, k_tiles, 4, 0.3 * pl.I, (double)M * N);
+    } else if (tiles < 256) {
+      // small-tile kernels (two workgroups per CU hide each other's latency): smallest split
+      // that fills >= 90 % of a whole number of 256-workgroup rounds
+      double best_eff = 0;
+      for (int s = 1; s <= 16; ++s) {
+        if (s > 1 && k_tiles / s < 4) break;
+        const long wgs = tiles * s;
+        const double eff = (double)wgs / (double)((wgs + 255) / 256 * 256);
+        if (eff > best_eff + 1e-9) { best_eff = eff; pl.splits = s; }
+        if (eff >= 0.9) break;
+      }
+    }
+  }
   pl.k_per_split = ceil_div(k_tiles, pl.splits) * pl.bk;
   pl.splits = ceil_div(K, pl.k_per_split);
   return pl;
