@@ -134,9 +134,10 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 
 // ---------------------------------------------------------------------------
 // Main bf16 kernel.
-//   tile        BM = 32*I rows (I = 2,4,6,8) x 256 columns x 64 k per stage (128-byte
+//   tile        BM = 32*I rows (I = 2,4,6,8) x BN = 64*NB columns (NB = 4, or 2 when that
+//               fills the CUs better) x 64 k per stage (128-byte
 //               rows: every global request is a whole cache line)
-//   wavefronts  4 as 2 x 2, each owning (BM/2) x 128 = (I/2) x 4 MFMA tiles: the
+//   wavefronts  4 as 2 x 2, each owning (BM/2) x (BN/2) = (I/2) x NB MFMA tiles: the
 //               layout with the fewest LDS operand bytes per MFMA (LDS read bandwidth,
 //               not the matrix cores, limits narrower wavefront tiles).  With one
 //               wavefront per SIMD nothing else hides LDS latency, so the operand
@@ -164,17 +165,17 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //               workgroups that share a weight tile run back to back on one L2.
 // Requires K % 64 == 0 and k_per_split % 64 == 0.
 // ---------------------------------------------------------------------------
-constexpr int DMA_BN = 256, DMA_BK = 64, DMA_CP = DMA_BN + 4;
+constexpr int DMA_BK = 64;
 // Two rings: the activation tile (mostly L2 hits) is double-buffered, the weight tile (streamed
 // from HBM, long latency) gets every remaining stage that fits in 160 KB, up to 4.
 constexpr int DMA_SA = 2;
-constexpr int dma_w_stages(int I) {
+constexpr int dma_w_stages(int I, int BN) {
   const int left = 160 * 1024 - DMA_SA * 32 * I * 128;
-  return left / (DMA_BN * 128) > 4 ? 4 : left / (DMA_BN * 128);
+  return left / (BN * 128) > 4 ? 4 : left / (BN * 128);
 }
-constexpr int dma_smem_bytes(int I) {
-  const int ring = DMA_SA * 32 * I * 128 + dma_w_stages(I) * DMA_BN * 128;
-  const int park = (I < 4 ? 32 * I : 128) * DMA_CP * 4;
+constexpr int dma_smem_bytes(int I, int BN) {
+  const int ring = DMA_SA * 32 * I * 128 + dma_w_stages(I, BN) * BN * 128;
+  const int park = (I < 4 ? 32 * I : 128) * (BN + 4) * 4;
   return ring > park ? ring : park;
 }
 
@@ -193,15 +194,15 @@ __device__ __forceinline__ void lds_pin(bf16x8 &f) { asm volatile("" : "+v"(f));
 template <int N> __device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-template <int I, int EPI>
+template <int I, int NB, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
-  constexpr int BM = 32 * I, SW = dma_w_stages(I);
-  constexpr int A_STAGE = BM * 128, W_STAGE = DMA_BN * 128, W_RING = DMA_SA * A_STAGE;
-  constexpr int LA = BM / 32, LW = DMA_BN / 32;          // 16-byte loads per lane per tile (8 rows x 4 waves each)
+  constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN), DMA_CP = BN + 4;
+  constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128, W_RING = DMA_SA * A_STAGE;
+  constexpr int LA = BM / 32, LW = BN / 32;              // 16-byte loads per lane per tile (8 rows x 4 waves each)
   static_assert(SW >= 3, "the vmcnt bookkeeping below assumes at least 3 weight stages");
   constexpr int IH = I / 2;                              // row blocks per wavefront
-  constexpr int NF = IH + 4;                             // operand reads per k-step per wavefront
-  constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? DMA_BN / 2 : DMA_BN;
+  constexpr int NF = IH + NB;                            // operand reads per k-step per wavefront
+  constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;               // 2 x 2 wavefronts, (BM/2) x 128 each
@@ -234,12 +235,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
     const bf16 *wrow;
     if (EPI == EPI_SWIGLU) {
-      // each wavefront column block of 128 tile columns holds 64 gate columns followed by the
-      // SAME 64 up columns, so that a lane ends up with gate and up of one output element
-      const int which = (r >> 6) & 1, oc = min(n0 + (r >> 7) * 64 + (r & 63), p.N - 1);
+      // each wavefront's half of the tile columns holds its gate columns followed by the SAME
+      // up columns, so that a lane ends up with gate and up of one output element
+      constexpr int WC = BN / 2, HC = BN / 4;          // columns per wavefront / per operand
+      const int which = (r % WC) / HC, oc = min(n0 + (r / WC) * HC + (r % HC), p.N - 1);
       wrow = reinterpret_cast<const bf16 *>(p.w[which]) + (size_t)oc * p.K;
     } else {
-      wrow = weight_row<bf16, EPI>(p, n0 + r, DMA_BN / 2, n0, r);
+      wrow = weight_row<bf16, EPI>(p, n0 + r, BN / 2, n0, r);
     }
     src_w[i] = wrow + chunk * 8 + kb;
   }
@@ -262,11 +264,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
       CB_GLDS16(src_w[i] + k0, smem + W_RING + (t % SW) * W_STAGE + (wave + 4 * i) * 1024);
   };
 
-  f32x16 acc[IH][4];
+  f32x16 acc[IH][NB];
 #pragma unroll
   for (int i = 0; i < IH; ++i)
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb)
+    for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][jb][r] = 0.f;
 
@@ -275,30 +277,34 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     int rd[4];                                                    // k-step ks reads chunk 2*ks + h
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) rd[ks] = (lane & 31) * 128 + (((2 * ks + h) ^ sw) << 4);
-    const int a_off = (wm * IH * 32) * 128, b_off = (wn * 128) * 128;
-    bf16x8 fa[2][IH], fb[2][4];
-    constexpr int NM = IH * 4;                         // MFMAs per k-step per wavefront
+    const int a_off = (wm * IH * 32) * 128, b_off = (wn * (BN / 2)) * 128;
+    bf16x8 fa[2][IH], fb[2][NB];
+    constexpr int NM = IH * NB;                        // MFMAs per k-step per wavefront
     constexpr int NL = LA + LW;                        // loads per tile per lane
     constexpr int NSLOT = NM > NF ? NM : NF;
     // operand read number idx (0..NF-1) into fragment buffer buf; base_w / base_a are the LDS
     // byte addresses of this lane's first weight / activation fragment of the k-step
     auto read_one = [&](unsigned base_w, unsigned base_a, int buf, int idx) {
-      switch (idx) {
-        case 0: lds_read16<0>(fb[buf][0], base_w); break;
-        case 1: lds_read16<4096>(fb[buf][1], base_w); break;
-        case 2: lds_read16<8192>(fb[buf][2], base_w); break;
-        case 3: lds_read16<12288>(fb[buf][3], base_w); break;
-        case 4: lds_read16<0>(fa[buf][0], base_a); break;
-        case 5: if (IH > 1) lds_read16<4096>(fa[buf][IH > 1 ? 1 : 0], base_a); break;
-        case 6: if (IH > 2) lds_read16<8192>(fa[buf][IH > 2 ? 2 : 0], base_a); break;
-        case 7: if (IH > 3) lds_read16<12288>(fa[buf][IH > 3 ? 3 : 0], base_a); break;
-        default: break;
+      if (idx < NB) {
+        switch (idx) {
+          case 0: lds_read16<0>(fb[buf][0], base_w); break;
+          case 1: lds_read16<4096>(fb[buf][1], base_w); break;
+          case 2: if (NB > 2) lds_read16<8192>(fb[buf][NB > 2 ? 2 : 0], base_w); break;
+          default: if (NB > 3) lds_read16<12288>(fb[buf][NB > 3 ? 3 : 0], base_w); break;
+        }
+      } else {
+        switch (idx - NB) {
+          case 0: lds_read16<0>(fa[buf][0], base_a); break;
+          case 1: if (IH > 1) lds_read16<4096>(fa[buf][IH > 1 ? 1 : 0], base_a); break;
+          case 2: if (IH > 2) lds_read16<8192>(fa[buf][IH > 2 ? 2 : 0], base_a); break;
+          default: if (IH > 3) lds_read16<12288>(fa[buf][IH > 3 ? 3 : 0], base_a); break;
+        }
       }
     };
     const unsigned lds0 = (unsigned)(size_t)smem;
     auto pin = [&](int buf) {
 #pragma unroll
-      for (int jb = 0; jb < 4; ++jb) lds_pin(fb[buf][jb]);
+      for (int jb = 0; jb < NB; ++jb) lds_pin(fb[buf][jb]);
 #pragma unroll
       for (int i = 0; i < IH; ++i) lds_pin(fa[buf][i]);
     };
@@ -312,8 +318,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
 #pragma unroll
       for (int j = 0; j < NSLOT; ++j) {
         if (j < NM)
-          acc[j / 4][j % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / 4], fb[buf][j % 4],
-                                                                     acc[j / 4][j % 4], 0, 0, 0);
+          acc[j / NB][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / NB], fb[buf][j % NB],
+                                                                       acc[j / NB][j % NB], 0, 0, 0);
         if (refill) {
 #pragma unroll
           for (int q = j * NL / NSLOT; q < (j + 1) * NL / NSLOT; ++q) issue_one(tl, q);
@@ -370,10 +376,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
         if (EPI == EPI_SWIGLU) {
           bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
 #pragma unroll
-          for (int jb = 0; jb < 2; ++jb) {
-            const int gc = n0 + wn * 64 + jb * 32 + ln;
+          for (int jb = 0; jb < NB / 2; ++jb) {
+            const int gc = n0 + wn * (BN / 4) + jb * 32 + ln;
             if (gc >= p.N) continue;
-            const float gt = acc[i][jb][r], up = acc[i][jb + 2][r];
+            const float gt = acc[i][jb][r], up = acc[i][jb + NB / 2][r];
             // silu(g) * u = g * u / (1 + 2^(-g log2 e))
             const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt);
             orow[gc] = (bf16)(gt * up * __builtin_amdgcn_rcpf(den));
@@ -382,8 +388,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
           if (p.splits > 1) {
             float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
 #pragma unroll
-            for (int jb = 0; jb < 4; ++jb) {
-              const int gc = n0 + wn * 128 + jb * 32 + ln;
+            for (int jb = 0; jb < NB; ++jb) {
+              const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
               if (gc < p.N) prow[gc] = acc[i][jb][r];
             }
           } else {
@@ -391,8 +397,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
             const float *res = p.resid ? p.resid + (size_t)rr * p.N : nullptr;
             float *orow = p.out_f32 + (size_t)gr * p.N;
 #pragma unroll
-            for (int jb = 0; jb < 4; ++jb) {
-              const int gc = n0 + wn * 128 + jb * 32 + ln;
+            for (int jb = 0; jb < NB; ++jb) {
+              const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
               if (gc < p.N) orow[gc] = acc[i][jb][r] + (res ? res[gc] : 0.f);
             }
           }
@@ -417,17 +423,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
       const int ib = wm * IH + i;                            // this wavefront's row block
       if (ib >= i0 && ib < i0 + 4) {
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb)
+        for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int row = (ib - i0) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-            const int col = wn * 128 + jb * 32 + (lane & 31);
+            const int col = wn * (BN / 2) + jb * 32 + (lane & 31);
             sC[row * DMA_CP + col] = acc[i][jb][r];
           }
       }
     }
     __syncthreads();
-    lds_epilogue<bf16, EPI, DMA_BN>(sC, DMA_CP, nb * 32, m0 + i0 * 32, n0, z, p);
+    lds_epilogue<bf16, EPI, BN>(sC, DMA_CP, nb * 32, m0 + i0 * 32, n0, z, p);
   }
 }
 
@@ -612,7 +618,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p) {
 // ---------------------------------------------------------------------------
 struct GemmPlan {
   int kind;        // 0 float, 1 register-staged bf16, 2 direct-to-LDS bf16
-  int I;           // kind 2: row blocks per tile
+  int I, NB;       // kind 2: 32-row blocks per tile, 32-column blocks per wavefront (tile = 32I x 64NB)
   int bm, out_cols, bk;
   int tiles_m, tiles_n, splits, k_per_split;
 };
@@ -654,8 +660,17 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   } else if (K % DMA_BK == 0 && (epi == EPI_SWIGLU || (epi == EPI_F32 && K >= 8192))) {
     // measured: the big-tile kernel wins where N or K is large (gate/up, down projection);
     // the register-staged kernel with its finer tiles wins on the Q/K/V and output projections
-    pl.kind = 2; pl.I = pick_row_blocks(M); pl.bm = 32 * pl.I;
-    pl.out_cols = epi == EPI_SWIGLU ? DMA_BN / 2 : DMA_BN; pl.bk = DMA_BK;
+    pl.kind = 2; pl.I = pick_row_blocks(M); pl.bm = 32 * pl.I; pl.bk = DMA_BK;
+    // 256-column tiles unless 128-column tiles (lower arithmetic intensity: measured ~1.4x
+    // slower per flop) fill the rounds of 256 workgroups so much better that they still win,
+    // which happens when there is a single row of tiles (M <= 256)
+    pl.NB = 4;
+    if (epi == EPI_SWIGLU) {
+      const long t4 = (long)ceil_div(M, pl.bm) * ceil_div(N, 128), t2 = (long)ceil_div(M, pl.bm) * ceil_div(N, 64);
+      const double c4 = (double)((t4 + 255) / 256) * 2.0, c2 = (double)((t2 + 255) / 256) * 1.4;
+      if (c2 < c4) pl.NB = 2;
+    }
+    pl.out_cols = (epi == EPI_SWIGLU ? 32 : 64) * pl.NB;
   } else {
     pl.kind = 1; pl.bm = BM16; pl.out_cols = epi == EPI_SWIGLU ? BN16 / 2 : BN16; pl.bk = BK16;
   }
@@ -728,18 +743,18 @@ bool gemm_needs_reduce(const GemmArgs &g) {
   return fill_params(g, &p).splits > 1;
 }
 
-template <int I, int EPI>
+template <int I, int NB, int EPI>
 static void launch_dma(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
-  constexpr int smem = dma_smem_bytes(I);
+  constexpr int smem = dma_smem_bytes(I, 64 * NB);
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<I, EPI>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<I, NB, EPI>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
   const int nblk = ceil_div(pl.tiles_n, 8);
   const unsigned grid = 8u * nblk * pl.tiles_m * pl.splits;
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, EPI>), dim3(grid), dim3(256), smem, s, p, pl.tiles_m,
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI>), dim3(grid), dim3(256), smem, s, p, pl.tiles_m,
                      pl.tiles_n);
 }
 
@@ -757,11 +772,20 @@ static void launch_typed(const GemmPlan &pl, const GemmParams &p, hipStream_t s)
     }
     hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), kSmemBf16, s, p);
   } else {
-    switch (pl.I) {
-      case 2: launch_dma<2, EPI>(pl, p, s); break;
-      case 4: launch_dma<4, EPI>(pl, p, s); break;
-      case 6: launch_dma<6, EPI>(pl, p, s); break;
-      default: launch_dma<8, EPI>(pl, p, s); break;
+    if (pl.NB == 2) {
+      switch (pl.I) {
+        case 2: launch_dma<2, 2, EPI>(pl, p, s); break;
+        case 4: launch_dma<4, 2, EPI>(pl, p, s); break;
+        case 6: launch_dma<6, 2, EPI>(pl, p, s); break;
+        default: launch_dma<8, 2, EPI>(pl, p, s); break;
+      }
+    } else {
+      switch (pl.I) {
+        case 2: launch_dma<2, 4, EPI>(pl, p, s); break;
+        case 4: launch_dma<4, 4, EPI>(pl, p, s); break;
+        case 6: launch_dma<6, 4, EPI>(pl, p, s); break;
+        default: launch_dma<8, 4, EPI>(pl, p, s); break;
+      }
     }
   }
 }
