@@ -6,14 +6,16 @@
 // bf16 kernel (MFMA 32x32x16).  One workgroup = one kv head x a block of
 // "flattened queries" m = row * g + head_in_group, so the g query heads that share
 // a kv head sit side by side in the MFMA N dimension and every K/V tile staged in
-// LDS is used by all of them.  Each wavefront owns NQB blocks of 32 queries.
+// LDS is used by all of them.  Each of the 8 wavefronts owns a block of 32 queries.
 // Both products are computed transposed,
 //     S^T[key, query] = K Q^T            O^T[channel, query] += V^T P^T
 // so that a lane always holds values of ONE query (column = lane % 32): the running
 // max / sum and the rescaling of O need no cross-lane traffic except one exchange
 // between the two half-waves, and the exponentiated scores are already laid out as
 // the B operand of the second product (they never leave registers).  The second
-// product contracts over keys, so V is stored transposed in LDS ([channel][key]).
+// product contracts over keys; V stays row-major in LDS and its operand is fetched with
+// the transposing LDS read (ds_read_b64_tr_b16).  K/V tiles are streamed through a 3-stage
+// LDS ring by direct global->LDS loads.
 //
 // float kernel: one wavefront per (row, query head), 64 keys per step, plain FMA.
 #include "common.h"
@@ -27,36 +29,43 @@ constexpr float kNegBig = -1.0e30f;
 
 // ---------------------------------------------------------------------------
 constexpr int BKV = 64;                 // keys per tile
-constexpr int VT_PITCH = BKV + 4;       // transposed V tile: [dh][BKV + 4] bf16
+constexpr int ATT_S = 3;                // LDS ring stages (K tile + V tile each)
 
-template <int DH, int NQB>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__ q,
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+template <int DH, int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restrict__ q,
                                                         const int32_t *__restrict__ q_pos, int n_rows,
                                                         const bf16 *__restrict__ kc,
                                                         const bf16 *__restrict__ vc, bf16 *__restrict__ o,
                                                         int n_q_heads, int n_kv_heads, float scale_log2e,
                                                         int split_tiles, float *__restrict__ part_o,
                                                         float *__restrict__ part_ml) {
-  constexpr int KP = DH + 8;            // K tile pitch (elements)
-  constexpr int KS = DH / 16;           // k-steps of the first product
-  constexpr int DB = DH / 32;           // 32-channel blocks of the output
-  constexpr int CH = DH / 8;            // 16-byte chunks per K/V row
-  constexpr int K_CHUNKS = BKV * CH / 256;        // per thread
-  constexpr int V_PAIRS = (BKV / 2) * CH / 256;   // per thread (two keys x 8 channels)
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16 *sK = reinterpret_cast<bf16 *>(smem_raw);   // [2][BKV * KP]
-  bf16 *sVt = sK + 2 * BKV * KP;                    // [2][DH * VT_PITCH]
+  // K and V tiles sit row-major in LDS ([key][channel], no padding) and are filled by direct
+  // global->LDS loads: one wavefront-wide 16-byte load writes 1 KB = RPI whole rows.  Instead of
+  // padding, the 16-byte chunk c of row r is stored in slot c ^ f(r), which makes both the
+  // 16-byte K operand reads and the transposing 8-byte V reads conflict-free.
+  constexpr int ROWB = DH * 2;            // bytes per row
+  constexpr int CH = DH / 8;              // 16-byte chunks per row
+  constexpr int RPI = 1024 / ROWB;        // rows per wavefront-wide load
+  constexpr int TILEB = BKV * ROWB;       // bytes of one K (or V) tile
+  constexpr int STAGE = 2 * TILEB;
+  constexpr int LPT = 2 * (BKV / RPI) / NW; // loads per lane per tile (K and V, NW wavefronts)
+  constexpr int WGQ = 32 * NQB * NW;        // flattened queries per workgroup
+  constexpr int KS = DH / 16;             // k-steps of the first product
+  constexpr int DB = DH / 32;             // 32-channel blocks of the output
+  extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, h = lane >> 5;
   const int g = n_q_heads / n_kv_heads;
   const int kvh = blockIdx.y;
   const int n_flat = n_rows * g;
-  const int m_wg = blockIdx.x * (128 * NQB);
+  const int m_wg = blockIdx.x * WGQ;
   const int kv_dim = n_kv_heads * DH;
 
   // causal bound of the workgroup = position of its last valid row
-  const int last_m = min(m_wg + 128 * NQB, n_flat) - 1;
+  const int last_m = min(m_wg + WGQ, n_flat) - 1;
   const int kv_len = q_pos[last_m / g] + 1;
   const int n_tiles_all = (kv_len + BKV - 1) / BKV;
   // KV split: workgroup z of gridDim.z handles tiles [t_begin, n_tiles) of the causal range and
@@ -100,49 +109,69 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
       for (int i = 0; i < 16; ++i) oacc[b][d][i] = 0.f;
   }
 
-  // global -> register -> LDS staging of one K/V tile
-  bf16x8 rk[K_CHUNKS], rv[V_PAIRS][2];
-  auto gload = [&](int t0) {
-#pragma unroll
-    for (int i = 0; i < K_CHUNKS; ++i) {
-      const int id = tid + i * 256, key = id / CH, c = id % CH;
-      const int row = min(t0 + key, kv_len - 1);
-      rk[i] = *reinterpret_cast<const bf16x8 *>(kc + (size_t)row * kv_dim + kvh * DH + c * 8);
-    }
-#pragma unroll
-    for (int i = 0; i < V_PAIRS; ++i) {
-      const int id = tid + i * 256, kp = id % (BKV / 2), c = id / (BKV / 2);
-      const int r0 = min(t0 + 2 * kp, kv_len - 1), r1 = min(t0 + 2 * kp + 1, kv_len - 1);
-      rv[i][0] = *reinterpret_cast<const bf16x8 *>(vc + (size_t)r0 * kv_dim + kvh * DH + c * 8);
-      rv[i][1] = *reinterpret_cast<const bf16x8 *>(vc + (size_t)r1 * kv_dim + kvh * DH + c * 8);
-    }
-  };
-  auto sstore = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < K_CHUNKS; ++i) {
-      const int id = tid + i * 256, key = id / CH, c = id % CH;
-      *reinterpret_cast<bf16x8 *>(sK + st * BKV * KP + key * KP + c * 8) = rk[i];
-    }
-#pragma unroll
-    for (int i = 0; i < V_PAIRS; ++i) {
-      const int id = tid + i * 256, kp = id % (BKV / 2), c = id / (BKV / 2);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        bf16x2 pr = {rv[i][0][e], rv[i][1][e]};
-        *reinterpret_cast<bf16x2 *>(sVt + st * DH * VT_PITCH + (c * 8 + e) * VT_PITCH + 2 * kp) = pr;
-      }
-    }
-  };
+  // swizzle: DH = 128 rows start at bank 0 -> 16 slots, f(r) = r & 15; DH = 64 rows alternate
+  // between the two bank halves -> 8 slots, f(r) = (r >> 1) & 7
+  auto fswz = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
 
-  gload(t_begin * BKV);
-  sstore(t_begin & 1);
-  __syncthreads();
+  // ---- global -> LDS: this lane's share of the loads of one tile ----
+  int ld_row[LPT], ld_col[LPT];           // tile row, element offset of the (de-swizzled) chunk
+  bool ld_v[LPT];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) {
+    const int gi = wave + NW * i;                      // load group: first K groups, then V groups
+    ld_v[i] = gi >= BKV / RPI;
+    const int gl = ld_v[i] ? gi - BKV / RPI : gi;
+    ld_row[i] = gl * RPI + lane / CH;
+    ld_col[i] = ((lane % CH) ^ fswz(ld_row[i])) * 8 + kvh * DH;
+  }
+  const bf16 *ld_base[LPT];
+#pragma unroll
+  for (int i = 0; i < LPT; ++i) ld_base[i] = (ld_v[i] ? vc : kc) + (size_t)ld_row[i] * kv_dim + ld_col[i];
+  auto issue = [&](int t) {
+    const int t0 = min(t, n_tiles_all - 1) * BKV;     // clamped: every call issues LPT loads
+    char *stage = smem + (t % ATT_S) * STAGE;
+    const bool whole = t0 + BKV <= kv_len;             // uniform: no row of the tile is past the bound
+    const size_t adv = (size_t)t0 * kv_dim;
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const bf16 *src = ld_base[i] + adv;
+      if (!whole) {
+        const int row = min(t0 + ld_row[i], kv_len - 1);
+        src = (ld_v[i] ? vc : kc) + (size_t)row * kv_dim + ld_col[i];
+      }
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                       (__attribute__((address_space(3))) void *)(stage + (wave + NW * i) * 1024),
+                                       16, 0, 0);
+    }
+  };
+  // ---- LDS read offsets of this lane ----
+  int k_off[KS];                                       // K operand: row ln (+32 kb), chunk 2 ks + h
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) k_off[ks] = ln * ROWB + (((2 * ks + h) ^ fswz(ln)) << 4);
+  // V operand through the transposing read: lane s of a 16-lane block passes the address of
+  // 4 channels (8 bytes) of key K0 + s/4 and receives, for channel C0 + s, the 4 keys K0..K0+3
+  int v_off[DB][2];
+  {
+    const int s16 = lane & 15, qb = lane >> 4;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const int key = 8 * a + 4 * (qb >> 1) + (s16 >> 2);               // + 16 u per MFMA
+        const int ch = d * 32 + 16 * (qb & 1) + 4 * (s16 & 3);
+        v_off[d][a] = TILEB + key * ROWB + (((ch >> 3) ^ fswz(key)) << 4) + (ch & 7) * 2;
+      }
+  }
+
+#pragma unroll
+  for (int sI = 0; sI < ATT_S - 1; ++sI) issue(t_begin + sI);
   for (int t = t_begin; t < n_tiles; ++t) {
     const int t0 = t * BKV;
-    if (t + 1 < n_tiles) gload(t0 + BKV);
+    __builtin_amdgcn_s_waitcnt(((ATT_S - 2) * LPT) | (7 << 4) | (0 << 8));   // tile t landed; my LDS reads done
+    asm volatile("s_barrier" ::: "memory");
+    issue(t + ATT_S - 1);
     if (t0 <= wave_max_pos) {  // wave-uniform: tiles wholly in this wave's future are skipped
-      const bf16 *ck = sK + (t & 1) * BKV * KP;
-      const bf16 *cv = sVt + (t & 1) * DH * VT_PITCH;
+      const char *ck = smem + (t % ATT_S) * STAGE;
       // ---- S^T = K Q^T ----
       f32x16 sacc[NQB][2];
 #pragma unroll
@@ -151,14 +180,19 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) sacc[b][kb][i] = 0.f;
+      {
+        // K operand reads run two steps ahead of the MFMAs that use them (step = (ks, kb))
+        constexpr int NSTEP = 2 * KS;
+        bf16x8 kf[3];
+        kf[0] = *reinterpret_cast<const bf16x8 *>(ck + k_off[0]);
+        kf[1] = *reinterpret_cast<const bf16x8 *>(ck + 32 * ROWB + k_off[0]);
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ck + (kb * 32 + ln) * KP + ks * 16 + 8 * h);
+        for (int st = 0; st < NSTEP; ++st) {
+          if (st + 2 < NSTEP)
+            kf[(st + 2) % 3] = *reinterpret_cast<const bf16x8 *>(ck + ((st + 2) & 1) * 32 * ROWB + k_off[(st + 2) >> 1]);
 #pragma unroll
           for (int b = 0; b < NQB; ++b)
-            sacc[b][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[b][ks], sacc[b][kb], 0, 0, 0);
+            sacc[b][st & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st % 3], qf[b][st >> 1], sacc[b][st & 1], 0, 0, 0);
         }
       }
       // ---- online softmax (per lane = per query), in the raw score domain: p = 2^((s - m) c) ----
@@ -206,23 +240,29 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16 *__restrict__
         row_sum[b] += psum;
       }
       // ---- O^T += V^T P^T ----
+      {
+        // V operand (two transposing reads) fetched one step ahead; step = (u, d)
+        constexpr int NSTEP = 4 * DB;
+        union VF { s16x4 s[2]; bf16x8 b; } vf[2];
+        auto vread = [&](int st, VF &dst) {
+          const int u = st / DB, d = st % DB;
+          dst.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4 *)(ck + u * 16 * ROWB + v_off[d][0]));
+          dst.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4 *)(ck + u * 16 * ROWB + v_off[d][1]));
+        };
+        vread(0, vf[0]);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int d = 0; d < DB; ++d) {
-          const bf16 *vp = cv + (d * 32 + ln) * VT_PITCH + 16 * u + 4 * h;
-          const bf16x4 v0 = *reinterpret_cast<const bf16x4 *>(vp);
-          const bf16x4 v1 = *reinterpret_cast<const bf16x4 *>(vp + 8);
-          const bf16x8 vf = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        for (int st = 0; st < NSTEP; ++st) {
+          if (st + 1 < NSTEP) vread(st + 1, vf[(st + 1) & 1]);
 #pragma unroll
           for (int b = 0; b < NQB; ++b)
-            oacc[b][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[b][u], oacc[b][d], 0, 0, 0);
+            oacc[b][st % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st & 1].b, pf[b][st / DB], oacc[b][st % DB], 0, 0, 0);
         }
       }
     }
-    if (t + 1 < n_tiles) sstore((t + 1) & 1);
-    __syncthreads();
   }
+  __builtin_amdgcn_s_waitcnt(7 << 4);      // drain the clamped tail loads before the workgroup ends
   if (gridDim.z > 1) {
     // ---- partial results: O (un-normalised), running max and sum per (kv head, query, split) ----
 #pragma unroll
@@ -357,14 +397,15 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
     if (lane + 64 * c < DH) orow[lane + 64 * c] = acc[c] / run_sum;
 }
 
+// Workgroup = 8 wavefronts x 32 flattened queries (two wavefronts per SIMD: one runs its softmax
+// on the VALU while the other feeds the matrix core, and neither needs more than 256 registers).
+constexpr int ATT_NW = 8, ATT_WGQ = 32 * ATT_NW;
+
 // Split plan of the bf16 kernel: few query workgroups (the selective layers) leave most CUs
 // idle, so the key range is cut into n_splits pieces handled by separate workgroups.
-static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *nqb, int *n_splits,
-                            int *split_tiles) {
+static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *n_splits, int *split_tiles) {
   const long n_flat = (long)n_rows * (hq / hkv);
-  const bool big = ((n_flat + 255) / 256) * hkv >= 512;
-  *nqb = big ? 2 : 1;
-  const long base = ((n_flat + 128 * *nqb - 1) / (128 * *nqb)) * hkv;
+  const long base = ((n_flat + ATT_WGQ - 1) / ATT_WGQ) * hkv;
   const int max_tiles = (n_tokens + BKV - 1) / BKV;
   int ns = 1;
   if (base < 384) {
@@ -378,8 +419,8 @@ static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *nqb,
 
 size_t attention_partial_floats(int dtype, int n_rows, int hq, int hkv, int dh, int n_tokens) {
   if (dtype == 0 || n_rows == 0) return 0;
-  int nqb, ns, st;
-  attn_split_plan(n_rows, hq, hkv, n_tokens, &nqb, &ns, &st);
+  int ns, st;
+  attn_split_plan(n_rows, hq, hkv, n_tokens, &ns, &st);
   if (ns <= 1) return 0;
   return (size_t)n_rows * hq * ns * (dh + 2);
 }
@@ -401,31 +442,31 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int 
   }
   const int g = hq / hkv;
   const long n_flat = (long)n_rows * g;
-  int nqb, n_splits, split_tiles;
-  attn_split_plan(n_rows, hq, hkv, n_tokens, &nqb, &n_splits, &split_tiles);
+  int n_splits, split_tiles;
+  attn_split_plan(n_rows, hq, hkv, n_tokens, &n_splits, &split_tiles);
   if (n_splits > 1 && (!partial || partial_floats < (size_t)n_rows * hq * n_splits * (dh + 2))) {
     n_splits = 1;                                    // no scratch: one workgroup walks all keys
     split_tiles = (n_tokens + BKV - 1) / BKV;
   }
+  const int wgq = ATT_WGQ;
   float *part_o = partial;
   float *part_ml = partial ? partial + (size_t)n_rows * hq * n_splits * dh : nullptr;
-#define CB_ATTN(DH_, NQB_)                                                                          \
+#define CB_ATTN(DH_, NQB_, NW_)                                                                     \
   do {                                                                                              \
-    constexpr int smem = 2 * (BKV * (DH_ + 8) + DH_ * VT_PITCH) * 2;                                \
+    constexpr int smem = ATT_S * 2 * BKV * DH_ * 2;                                                 \
     static bool attr_set = false;                                                                   \
     if (!attr_set) {                                                                                \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<DH_, NQB_>),       \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<DH_, NQB_, NW_>),  \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);                  \
       attr_set = true;                                                                              \
     }                                                                                               \
-    hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_>),                                               \
-                       dim3((unsigned)((n_flat + 128 * NQB_ - 1) / (128 * NQB_)), hkv, n_splits),   \
-                       dim3(256), smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc,        \
-                       (const bf16 *)vc, (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o,      \
-                       part_ml);                                                                    \
+    hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_, NW_>),                                          \
+                       dim3((unsigned)((n_flat + wgq - 1) / wgq), hkv, n_splits), dim3(64 * NW_),   \
+                       smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc, (const bf16 *)vc, \
+                       (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml);              \
   } while (0)
-  if (dh == 64) { if (nqb == 2) CB_ATTN(64, 2); else CB_ATTN(64, 1); }
-  else          { if (nqb == 2) CB_ATTN(128, 2); else CB_ATTN(128, 1); }
+  if (dh == 64) CB_ATTN(64, 1, ATT_NW);
+  else CB_ATTN(128, 1, ATT_NW);
 #undef CB_ATTN
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
@@ -433,10 +474,10 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int 
   const dim3 mgrid((unsigned)((total + 255) / 256));
   if (dh == 64)
     hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
-                       (bf16 *)o, hq, hkv, n_splits, split_tiles, 128 * nqb);
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq);
   else
     hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
-                       (bf16 *)o, hq, hkv, n_splits, split_tiles, 128 * nqb);
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq);
   return hipGetLastError();
 }
 
