@@ -3,16 +3,16 @@
 // C[M, N] = A[M, K] * W[N, K]^T with both operands K-contiguous.
 //
 // bf16 storage: v_mfma_f32_32x32x16_bf16 with float accumulation.  The main kernel
-// (gemm_bf16_dma_kernel) streams (32*I) x 256 x 32 tiles through a 4-stage LDS ring
-// filled by direct global->LDS loads, with an XCD-aware tile order; a simpler
-// register-staged 128x128x64 kernel covers K that is not a multiple of 32.
+// (gemm_bf16_dma_kernel) streams (32*I) x (64*NB) x 64 tiles through LDS rings filled by
+// direct global->LDS loads, with an XCD-aware tile order; a simpler register-staged
+// 128x128x64 kernel covers K that is not a multiple of 64.
 // float storage: plain FMA tiles (parity mode, not tuned).
-// Every kernel ends by parking its accumulator tile in LDS; one shared epilogue
-// then walks it row-major, 4 adjacent columns per lane, which gives the rotary
-// embedding its (2i, 2i+1) pair in one lane, SwiGLU its gate and up value in one
-// lane, and coalesced stores.  A problem with too few tiles to fill 256 CUs is split
-// along K: the main kernel then stores raw partial sums and a second kernel adds them
-// in a fixed order (no atomics: bitwise reproducible) and applies the epilogue.
+// The SwiGLU and float-output epilogues work straight from the accumulator registers;
+// the segment epilogue parks the tile in LDS and walks it row-major, 4 adjacent columns
+// per lane, which gives the rotary embedding its (2i, 2i+1) pair in one lane and 8-byte
+// stores.  A problem with too few tiles to fill the chip is split along K: the main
+// kernel then stores raw partial sums and a second kernel adds them in a fixed order
+// (no atomics: bitwise reproducible) and applies the epilogue.
 // Epilogues:
 //   EPI_SEG    up to three column segments (Q | K | V), each with its own weight
 //              matrix, destination, optional destination-row map (scatter into the
@@ -170,6 +170,7 @@ constexpr int DMA_BK = 64;
 // from HBM, long latency) gets every remaining stage that fits in 160 KB, up to 4.
 constexpr int DMA_SA = 2;
 constexpr int dma_w_stages(int I, int BN) {
+  if (BN == 128 && I <= 4) return 3;                   // <= 80 KB: two workgroups per CU
   const int left = 160 * 1024 - DMA_SA * 32 * I * 128;
   return left / (BN * 128) > 4 ? 4 : left / (BN * 128);
 }
@@ -637,62 +638,76 @@ static int pick_row_blocks(int M) {
   return best;
 }
 
-// K-split count from a small cost model (microseconds): rounds of 256 workgroups, each walking
-// k_tiles / s tiles of t_tile us, plus the traffic of the partial sums (written and read back
-// once per split at ~4 TB/s) when s > 1.  t_tile comes from measurements of the two kernels.
-static int pick_splits(long tiles, int k_tiles, int min_k_tiles, double t_tile, double mn) {
-  int best = 1;
-  double best_cost = 1e30;
-  const double reduce_us = mn * 8.0 / 4.0e6;           // bytes / (4 TB/s) in us, per split
-  for (int s = 1; s <= 16; ++s) {
-    if (s > 1 && k_tiles / s < min_k_tiles) break;
-    const double rounds = (double)((tiles * s + 255) / 256);
-    const double cost = rounds * ((k_tiles + s - 1) / s) * t_tile + (s > 1 ? s * reduce_us + 6.0 : 0.0);
-    if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+// Tile shape and K split of the direct-to-LDS kernel for the Q/K/V, output and down projections,
+// from a cost model in microseconds.  t_full = measured time of one 64-deep k-tile when every
+// slot of the chip is busy (a slot = one resident workgroup: two per CU for the tiles whose
+// rings fit twice into LDS, else one); a round that fills only part of the slots runs faster
+// per tile because fewer workgroups share the L2 -> LDS path; split partial sums cost their
+// round trip through memory.
+struct DmaShape { int I, NB; double t_full; };
+// Whole-prefill timings decided the candidate set: adding the 8x2, 4x4 and 6x4 tiles changed
+// nothing beyond noise, and 64-row tiles lost wherever more than 64 rows exist.
+static const DmaShape kDmaShapes[] = {{2, 2, 1.00}, {4, 2, 1.45}, {6, 2, 1.15}, {8, 4, 2.60}};
+
+static void pick_dma_plan(int M, int N, int K, GemmPlan *pl) {
+  const int k_tiles = K / DMA_BK;
+  const double reduce_us = (double)M * N * 8.0 / 4.0e6;   // per split: written once, read once at ~4 TB/s
+  double best = 1e30;
+  for (const DmaShape &c : kDmaShapes) {
+    if (c.I == 2 && M > 64) continue;
+    const int bm = 32 * c.I, bn = 64 * c.NB;
+    const int slots = dma_smem_bytes(c.I, bn) <= 80 * 1024 ? 512 : 256;
+    const long tiles = (long)ceil_div(M, bm) * ceil_div(N, bn);
+    for (int sp = 1; sp <= 16; ++sp) {
+      if (sp > 1 && k_tiles / sp < 4) break;
+      const long wgs = tiles * sp;
+      const long full = wgs / slots;
+      const double last = (double)(wgs - full * slots) / slots;          // fill of the last round
+      const double relief = slots == 512 ? 0.6 : 0.3;
+      const double per_tile = full * c.t_full + (last > 0 ? c.t_full * (1.0 - relief + relief * last) : 0.0);
+      const double cost = per_tile * ceil_div(k_tiles, sp) + (sp > 1 ? sp * reduce_us + 6.0 : 0.0);
+      if (cost < best - 1e-9) { best = cost; pl->I = c.I; pl->NB = c.NB; pl->splits = sp; }
+    }
   }
-  return best;
 }
 
 static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   GemmPlan pl = {};
+  pl.splits = 1;
   if (dtype == 0) {
     pl.kind = 0; pl.bm = BM32; pl.out_cols = epi == EPI_SWIGLU ? BN32 / 2 : BN32; pl.bk = BK32;
-  } else if (K % DMA_BK == 0 && (epi == EPI_SWIGLU || (epi == EPI_F32 && K >= 8192))) {
-    // measured: the big-tile kernel wins where N or K is large (gate/up, down projection);
-    // the register-staged kernel with its finer tiles wins on the Q/K/V and output projections
-    pl.kind = 2; pl.I = pick_row_blocks(M); pl.bm = 32 * pl.I; pl.bk = DMA_BK;
+  } else if (K % DMA_BK != 0) {
+    pl.kind = 1; pl.bm = BM16; pl.out_cols = epi == EPI_SWIGLU ? BN16 / 2 : BN16; pl.bk = BK16;
+  } else if (epi == EPI_SWIGLU) {
+    pl.kind = 2; pl.I = pick_row_blocks(M); pl.bk = DMA_BK;
     // 256-column tiles unless 128-column tiles (lower arithmetic intensity: measured ~1.4x
     // slower per flop) fill the rounds of 256 workgroups so much better that they still win,
     // which happens when there is a single row of tiles (M <= 256)
     pl.NB = 4;
-    if (epi == EPI_SWIGLU) {
-      const long t4 = (long)ceil_div(M, pl.bm) * ceil_div(N, 128), t2 = (long)ceil_div(M, pl.bm) * ceil_div(N, 64);
-      const double c4 = (double)((t4 + 255) / 256) * 2.0, c2 = (double)((t2 + 255) / 256) * 1.4;
-      if (c2 < c4) pl.NB = 2;
-    }
-    pl.out_cols = (epi == EPI_SWIGLU ? 32 : 64) * pl.NB;
+    const long t4 = (long)ceil_div(M, 32 * pl.I) * ceil_div(N, 128), t2 = (long)ceil_div(M, 32 * pl.I) * ceil_div(N, 64);
+    const double c4 = (double)((t4 + 255) / 256) * 2.0, c2 = (double)((t2 + 255) / 256) * 1.4;
+    if (c2 < c4) pl.NB = 2;
   } else {
-    pl.kind = 1; pl.bm = BM16; pl.out_cols = epi == EPI_SWIGLU ? BN16 / 2 : BN16; pl.bk = BK16;
+    pl.kind = 2; pl.bk = DMA_BK;
+    pick_dma_plan(M, N, K, &pl);
+  }
+  if (pl.kind == 2) {
+    pl.bm = 32 * pl.I;
+    pl.out_cols = (epi == EPI_SWIGLU ? 32 : 64) * pl.NB;
   }
   pl.tiles_m = ceil_div(M, pl.bm);
   pl.tiles_n = ceil_div(N, pl.out_cols);
-  pl.splits = 1;
   const int k_tiles = ceil_div(K, pl.bk);
   const long tiles = (long)pl.tiles_m * pl.tiles_n;
-  if (epi != EPI_SWIGLU) {
-    if (pl.kind == 2) {
-      pl.splits = pick_splits(tiles, k_tiles, 4, 0.3 * pl.I, (double)M * N);
-    } else if (tiles < 256) {
-      // small-tile kernels (two workgroups per CU hide each other's latency): smallest split
-      // that fills >= 90 % of a whole number of 256-workgroup rounds
-      double best_eff = 0;
-      for (int s = 1; s <= 16; ++s) {
-        if (s > 1 && k_tiles / s < 4) break;
-        const long wgs = tiles * s;
-        const double eff = (double)wgs / (double)((wgs + 255) / 256 * 256);
-        if (eff > best_eff + 1e-9) { best_eff = eff; pl.splits = s; }
-        if (eff >= 0.9) break;
-      }
+  if (pl.kind == 1 && epi != EPI_SWIGLU && tiles < 256) {
+    // smallest split that fills >= 90 % of a whole number of 256-workgroup rounds
+    double best_eff = 0;
+    for (int sp = 1; sp <= 16; ++sp) {
+      if (sp > 1 && k_tiles / sp < 4) break;
+      const long wgs = tiles * sp;
+      const double eff = (double)wgs / (double)((wgs + 255) / 256 * 256);
+      if (eff > best_eff + 1e-9) { best_eff = eff; pl.splits = sp; }
+      if (eff >= 0.9) break;
     }
   }
   pl.k_per_split = ceil_div(k_tiles, pl.splits) * pl.bk;
