@@ -91,6 +91,7 @@ size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim + 2 * kv_dim, d));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, q_dim));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, m.d_ff));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, mm, m.d_ff, d));
     // the attention KV split borrows the same scratch (the two are never live together)
     need = std::max(need, attention_partial_floats(m.dtype, mm, m.n_q_heads, m.n_kv_heads, m.head_dim,
                                                    c->max_tokens));
@@ -263,10 +264,15 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   u.dtype = dt; u.a = ws.xn; u.lda = d; u.M = rows; u.K = d; u.epi = EPI_SWIGLU; u.n_seg = 2;
   u.seg[0] = {w->w_gate, F, ws.act, F, nullptr, 0};
   u.seg[1] = {w->w_up, F, nullptr, 0, nullptr, 0};
+  u.partial = ws.partial; u.partial_floats = ws.partial_floats;
   {
     ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * 2 * F,
                  ((double)2 * F * d + (double)rows * d + (double)rows * F) * es);
     CB_HIP(launch_gemm(u, s));
+  }
+  if (gemm_needs_reduce(u)) {
+    ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+    CB_HIP(launch_gemm_reduce(u, s));
   }
   f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = w->w_down;
   f.out_f32 = h_out; f.resid = ws.hmid; f.resid_rows = nullptr;

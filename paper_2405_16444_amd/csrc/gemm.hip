@@ -44,6 +44,9 @@ struct GemmParams {
   const int32_t *resid_rows;
   float *partial;
   int splits, k_per_split;
+  // EPI_SWIGLU: workgroup ids >= tail_first share the tiles of the last, partly filled round of
+  // workgroups, tail_splits of them per tile, each over tail_k_per_split of K
+  int tail_first, tail_splits, tail_k_per_split;
 };
 
 // weight row that feeds tile column gc (clamped into range)
@@ -195,6 +198,73 @@ __device__ __forceinline__ void lds_pin(bf16x8 &f) { asm volatile("" : "+v"(f));
 template <int N> __device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// silu(gate) * up from one wavefront's accumulators of a (32*I) x (64*NB) tile: blocks
+// 0..NB/2-1 of a lane hold gate columns, blocks NB/2..NB-1 the same columns of the up matrix;
+// lane l holds column (l % 32) of each block and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row block.
+template <int I, int NB>
+__device__ __forceinline__ void swiglu_from_registers(const f32x16 (&acc)[I / 2][NB], const GemmParams &p,
+                                                      int m0, int n0, int wm, int wn, int lane) {
+  constexpr int IH = I / 2, BN = 64 * NB;
+  const int h = lane >> 5, ln = lane & 31;
+#pragma unroll
+  for (int i = 0; i < IH; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int gr = m0 + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+      if (gr >= p.M) continue;
+      bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
+#pragma unroll
+      for (int jb = 0; jb < NB / 2; ++jb) {
+        const int gc = n0 + wn * (BN / 4) + jb * 32 + ln;
+        if (gc >= p.N) continue;
+        const float gt = acc[i][jb][r], up = acc[i][jb + NB / 2][r];
+        // silu(g) * u = g * u / (1 + 2^(-g log2 e))
+        const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt);
+        orow[gc] = (bf16)(gt * up * __builtin_amdgcn_rcpf(den));
+      }
+    }
+  }
+}
+
+// Completes the tiles that several workgroups of the SwiGLU launch shared along K.  The partial
+// sums lie in register order: [slot][split][wavefront][row block i][column block jb][r][lane].
+// One wavefront here owns one (wavefront, i, gate block jb) unit of a tile: it adds the gate and
+// the up block over the splits in ascending K order and applies the epilogue.
+template <int I, int NB>
+__global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  constexpr int IH = I / 2, BM = 32 * I, BN = 64 * NB, HB = NB / 2;
+  constexpr int UNITS = 4 * IH * HB;                      // per tile
+  const int lane = threadIdx.x & 63;
+  const int slot = blockIdx.x / (UNITS / 4);
+  const int u = (blockIdx.x % (UNITS / 4)) * 4 + (threadIdx.x >> 6);
+  const int wave = u / (IH * HB), i = (u / HB) % IH, jb = u % HB;
+  const int xcd = slot & 7, j = (p.tail_first >> 3) + (slot >> 3);
+  const int nt = xcd + 8 * (j / tiles_m), mt = j % tiles_m;
+  if (nt >= tiles_n) return;
+  const float *pg = p.partial + (size_t)slot * p.tail_splits * (BM * BN) + (size_t)wave * (IH * NB * 16 * 64) +
+                    (size_t)(i * NB + jb) * (16 * 64) + lane;
+  float gate[16], up[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) gate[r] = up[r] = 0.f;
+  for (int zz = 0; zz < p.tail_splits; ++zz, pg += BM * BN) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      gate[r] += pg[r * 64];
+      up[r] += pg[(HB * 16 + r) * 64];
+    }
+  }
+  const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, ln = lane & 31;
+  const int gc = nt * (BN / 2) + wn * (BN / 4) + jb * 32 + ln;
+  if (gc >= p.N) return;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int gr = mt * BM + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+    if (gr >= p.M) continue;
+    const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate[r]);
+    reinterpret_cast<bf16 *>(p.dst[0])[(size_t)gr * p.ld[0] + gc] = (bf16)(gate[r] * up[r] * __builtin_amdgcn_rcpf(den));
+  }
+}
+
 template <int I, int NB, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN), DMA_CP = BN + 4;
@@ -209,15 +279,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   const int wm = wave >> 1, wn = wave & 1;               // 2 x 2 wavefronts, (BM/2) x 128 each
 
   // XCD-aware tile order
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, tail_z = -1;
+  if (EPI == EPI_SWIGLU && (int)blockIdx.x >= p.tail_first) {
+    const int v = ((int)blockIdx.x - p.tail_first) >> 3;
+    tail_z = v % p.tail_splits;
+    j = (p.tail_first >> 3) + v / p.tail_splits;
+  }
   const int nblk = (tiles_n + 7) >> 3;
   const int per_z = nblk * tiles_m;
   const int z = j / per_z, rem = j - z * per_z;
   const int nt = xcd + 8 * (rem / tiles_m), mt = rem % tiles_m;
   if (nt >= tiles_n) return;
   const int m0 = mt * BM, n0 = nt * OUT_COLS;
-  const int kb = z * p.k_per_split;
-  const int ke = min(p.K, kb + p.k_per_split);
+  const int kps = tail_z >= 0 ? p.tail_k_per_split : p.k_per_split;
+  const int kb = (tail_z >= 0 ? tail_z : z) * kps;
+  const int ke = min(p.K, kb + kps);
   const int nk = (ke - kb) / DMA_BK;
 
   // global source of each of this lane's loads per tile (row pointer + swizzled chunk)
@@ -364,6 +440,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     step(0, true, nk - 1, 3, false, 0);
     step(1, false, 0, 0, false, 0);
   }
+  if (EPI == EPI_SWIGLU && tail_z >= 0) {
+    // raw partial sums of a shared tile, in register order (each store is 256 contiguous bytes)
+    const int slot = (j - (p.tail_first >> 3)) * 8 + xcd;
+    float *pb = p.partial + ((size_t)slot * p.tail_splits + tail_z) * (BM * BN) + (size_t)wave * (IH * NB * 16 * 64);
+#pragma unroll
+    for (int i = 0; i < IH; ++i)
+#pragma unroll
+      for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) pb[((i * NB + jb) * 16 + r) * 64 + lane] = acc[i][jb][r];
+    return;
+  }
+  if (EPI == EPI_SWIGLU) {
+    swiglu_from_registers<I, NB>(acc, p, m0, n0, wm, wn, lane);
+    return;
+  }
   if (EPI != EPI_SEG) {
     // Epilogue straight from the accumulator registers: lane l holds column (l % 32) of each of
     // its four 32-column blocks and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row block.
@@ -374,34 +466,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
       for (int r = 0; r < 16; ++r) {
         const int gr = m0 + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
         if (gr >= p.M) continue;
-        if (EPI == EPI_SWIGLU) {
-          bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
+        if (p.splits > 1) {
+          float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
 #pragma unroll
-          for (int jb = 0; jb < NB / 2; ++jb) {
-            const int gc = n0 + wn * (BN / 4) + jb * 32 + ln;
-            if (gc >= p.N) continue;
-            const float gt = acc[i][jb][r], up = acc[i][jb + NB / 2][r];
-            // silu(g) * u = g * u / (1 + 2^(-g log2 e))
-            const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt);
-            orow[gc] = (bf16)(gt * up * __builtin_amdgcn_rcpf(den));
+          for (int jb = 0; jb < NB; ++jb) {
+            const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
+            if (gc < p.N) prow[gc] = acc[i][jb][r];
           }
         } else {
-          if (p.splits > 1) {
-            float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
+          const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
+          const float *res = p.resid ? p.resid + (size_t)rr * p.N : nullptr;
+          float *orow = p.out_f32 + (size_t)gr * p.N;
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-              const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
-              if (gc < p.N) prow[gc] = acc[i][jb][r];
-            }
-          } else {
-            const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
-            const float *res = p.resid ? p.resid + (size_t)rr * p.N : nullptr;
-            float *orow = p.out_f32 + (size_t)gr * p.N;
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-              const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
-              if (gc < p.N) orow[gc] = acc[i][jb][r] + (res ? res[gc] : 0.f);
-            }
+          for (int jb = 0; jb < NB; ++jb) {
+            const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
+            if (gc < p.N) orow[gc] = acc[i][jb][r] + (res ? res[gc] : 0.f);
           }
         }
       }
@@ -622,6 +701,9 @@ struct GemmPlan {
   int I, NB;       // kind 2: 32-row blocks per tile, 32-column blocks per wavefront (tile = 32I x 64NB)
   int bm, out_cols, bk;
   int tiles_m, tiles_n, splits, k_per_split;
+  int tail_first, tail_splits, tail_k_per_split;   // EPI_SWIGLU tail sharing (tail_splits <= 1: none)
+  long grid_ids;                                   // kind 2: workgroups of the main launch
+  size_t partial_floats;
 };
 
 static int pick_row_blocks(int M) {
@@ -712,6 +794,33 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   }
   pl.k_per_split = ceil_div(k_tiles, pl.splits) * pl.bk;
   pl.splits = ceil_div(K, pl.k_per_split);
+  pl.partial_floats = pl.splits > 1 ? (size_t)pl.splits * M * N : 0;
+  pl.tail_splits = 1;
+  if (pl.kind == 2) {
+    const long ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
+    pl.grid_ids = ids * pl.splits;
+    pl.tail_first = (int)pl.grid_ids;
+    if (epi == EPI_SWIGLU) {
+      // The last round of 256 workgroups, when less than half full, is shared: ts workgroups per
+      // tile, each over 1/ts of K, plus a fix-up launch.  Worth it when the time saved on the
+      // round exceeds the round trip of the partial sums (~4 TB/s) and the extra launch.
+      const long full = ids / 256 * 256, tail = ids - full;
+      int ts = tail > 0 ? (int)std::min<long>(4, 256 / tail) : 1;
+      while (ts > 1 && k_tiles / ts < 8) --ts;
+      if (ts > 1) {
+        const double t_tile = 0.3 * pl.I * (pl.NB == 4 ? 1.0 : 0.6);
+        const double saved = (k_tiles - ceil_div(k_tiles, ts)) * t_tile;
+        const double extra = (double)tail * ts * pl.bm * (64 * pl.NB) * 8.0 / 4.0e6 + 8.0;
+        if (saved > extra) {
+          pl.tail_first = (int)full;
+          pl.tail_k_per_split = ceil_div(k_tiles, ts) * pl.bk;
+          pl.tail_splits = ceil_div(K, pl.tail_k_per_split);
+          pl.grid_ids = full + tail * pl.tail_splits;
+          pl.partial_floats = (size_t)tail * pl.tail_splits * pl.bm * (64 * pl.NB);
+        }
+      }
+    }
+  }
   return pl;
 }
 
@@ -724,8 +833,7 @@ static int problem_n(const GemmArgs &g) {
 
 size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K) {
   if (M <= 0) return 0;
-  const GemmPlan pl = make_plan(dtype, epi, M, N, K);
-  return pl.splits > 1 ? (size_t)pl.splits * M * N : 0;
+  return make_plan(dtype, epi, M, N, K).partial_floats;
 }
 
 static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
@@ -743,19 +851,26 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   p.rope_tab = g.rope_tab; p.row_pos = g.row_pos; p.head_dim = g.head_dim;
   p.out_f32 = g.out_f32; p.resid = g.resid; p.resid_rows = g.resid_rows; p.partial = g.partial;
   GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K);
-  if (pl.splits > 1 && (!g.partial || g.partial_floats < (size_t)pl.splits * g.M * p.N)) {
-    pl.splits = 1;                                   // no scratch: one pass over K
+  if (pl.partial_floats > 0 && (!g.partial || g.partial_floats < pl.partial_floats)) {
+    // no scratch: one pass over K
+    if (pl.kind == 2) pl.grid_ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
+    pl.splits = 1;
     pl.k_per_split = ceil_div(g.K, pl.bk) * pl.bk;
+    pl.tail_splits = 1;
+    pl.tail_first = (int)pl.grid_ids;
+    pl.partial_floats = 0;
   }
   p.splits = pl.splits;
   p.k_per_split = pl.k_per_split;
+  p.tail_first = pl.tail_first; p.tail_splits = pl.tail_splits; p.tail_k_per_split = pl.tail_k_per_split;
   return pl;
 }
 
 bool gemm_needs_reduce(const GemmArgs &g) {
   if (g.M == 0) return false;
   GemmParams p;
-  return fill_params(g, &p).splits > 1;
+  const GemmPlan pl = fill_params(g, &p);
+  return pl.splits > 1 || pl.tail_splits > 1;
 }
 
 template <int I, int NB, int EPI>
@@ -767,10 +882,8 @@ static void launch_dma(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  const int nblk = ceil_div(pl.tiles_n, 8);
-  const unsigned grid = 8u * nblk * pl.tiles_m * pl.splits;
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI>), dim3(grid), dim3(256), smem, s, p, pl.tiles_m,
-                     pl.tiles_n);
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI>), dim3((unsigned)pl.grid_ids), dim3(256), smem, s, p,
+                     pl.tiles_m, pl.tiles_n);
 }
 
 template <int EPI>
@@ -819,6 +932,17 @@ hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
   if (g.M == 0) return hipSuccess;
   GemmParams p;
   const GemmPlan pl = fill_params(g, &p);
+  if (pl.tail_splits > 1) {
+    const dim3 tg((unsigned)((pl.grid_ids - pl.tail_first) / pl.tail_splits) * (pl.I / 2) * (pl.NB / 2));
+#define CB_TAIL(I_, NB_) hipLaunchKernelGGL((swiglu_tail_kernel<I_, NB_>), tg, dim3(256), 0, s, p, pl.tiles_m, pl.tiles_n)
+    if (pl.NB == 2) {
+      switch (pl.I) { case 2: CB_TAIL(2, 2); break; case 4: CB_TAIL(4, 2); break; case 6: CB_TAIL(6, 2); break; default: CB_TAIL(8, 2); break; }
+    } else {
+      switch (pl.I) { case 2: CB_TAIL(2, 4); break; case 4: CB_TAIL(4, 4); break; case 6: CB_TAIL(6, 4); break; default: CB_TAIL(8, 4); break; }
+    }
+#undef CB_TAIL
+    return hipGetLastError();
+  }
   if (pl.splits <= 1) return hipSuccess;
   const size_t total4 = (size_t)g.M * p.N / 4;
   const dim3 grid((unsigned)((total4 + 255) / 256));

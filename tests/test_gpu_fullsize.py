@@ -67,6 +67,7 @@ def run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, want_dev):
 @pytest.mark.parametrize("name,n_tokens,n_rows,n_suffix,k_keep", [
     ("mistral7b", 3136, 986, 64, 877),        # layer 2 of the gradual schedule: check on 922 candidates
     ("mistral7b", 3136, 359, 64, 231),        # last layer: 295 candidates -> 231
+    ("mistral7b", 3136, 589, 64, 461),        # 525 rows kept (flat 15 %): the gate/up GEMM's last round of tiles is shared along K
     ("yi34b", 3136, 525, 64, 400),            # 7 query heads per kv head, d = 7168
     ("llama70b", 4064, 300, 64, 200),         # 8 query heads per kv head, d = 8192, d_ff = 28672
     ("long32k", 32896, 700, 128, 500),        # 32 K-token cache: attention KV split + long positions
