@@ -171,15 +171,23 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim;
   g.partial = ws.partial; g.partial_floats = ws.partial_floats;
   const int32_t *sel_rows = nullptr;
+  bool q_all = false;
   if (check) {
     // K/V of every row that reached this layer (Sec. 6: "newly computed KV")
-    g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = 2;
+    // When nearly every candidate survives (gradual filtering), Q is projected for all candidates
+    // in the same launch and attention picks the kept rows through sel_rows; otherwise Q is
+    // projected after the selection, for the kept rows only.
+    q_all = (long)n * 4 <= (long)rows * 5;
+    g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = q_all ? 3 : 2;
     g.seg[0] = {w->wk, kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1};
     g.seg[1] = {w->wv, kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0};
+    g.seg[2] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
     g.row_pos = row_pos;
+    const int n_out = 2 * kv_dim + (q_all ? q_dim : 0);
     {
-      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * 2 * kv_dim,
-                   ((double)2 * kv_dim * d + (double)n * d + (double)n * 2 * kv_dim) * es);
+      // flops counted as the method needs them: Q only for the rows that are kept
+      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * 2 * kv_dim + (q_all ? 2.0 * rows * d * q_dim : 0.0),
+                   ((double)n_out * d + (double)n * d + (double)n * n_out) * es);
       CB_HIP(launch_gemm(g, s));
     }
     if (gemm_needs_reduce(g)) {
@@ -203,17 +211,19 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)rows * 4 * kv_dim * es);
       CB_HIP(launch_scatter_kv(dt, ws.kvnew, sel_rows, pos_out, rows, kc, vc, kv_dim, s));
     }
-    g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
-    g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
-    g.row_pos = pos_out;
-    {
-      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * q_dim,
-                   ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es);
-      CB_HIP(launch_gemm(g, s));
-    }
-    if (gemm_needs_reduce(g)) {
-      ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-      CB_HIP(launch_gemm_reduce(g, s));
+    if (!q_all) {
+      g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
+      g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
+      g.row_pos = pos_out;
+      {
+        ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * q_dim,
+                     ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es);
+        CB_HIP(launch_gemm(g, s));
+      }
+      if (gemm_needs_reduce(g)) {
+        ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
+        CB_HIP(launch_gemm_reduce(g, s));
+      }
     }
   } else {
     // every row is kept: one fused Q|K|V projection, K and V written straight into the cache
@@ -238,7 +248,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   }
   {
     ProfScope ps(c, s, CB_PROF_ATTN, 0, 0);
-    CB_HIP(launch_attention(dt, ws.qbuf, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads, m.n_kv_heads,
+    CB_HIP(launch_attention(dt, ws.qbuf, q_all ? sel_rows : nullptr, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads, m.n_kv_heads,
                             m.head_dim, n_tokens, ws.partial, ws.partial_floats, s));
   }
   // h = H + o Wo^T

@@ -40,7 +40,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
                                                         const bf16 *__restrict__ vc, bf16 *__restrict__ o,
                                                         int n_q_heads, int n_kv_heads, float scale_log2e,
                                                         int split_tiles, float *__restrict__ part_o,
-                                                        float *__restrict__ part_ml) {
+                                                        float *__restrict__ part_ml,
+                                                        const int32_t *__restrict__ q_rows) {
   // K and V tiles sit row-major in LDS ([key][channel], no padding) and are filled by direct
   // global->LDS loads: one wavefront-wide 16-byte load writes 1 KB = RPI whole rows.  Instead of
   // padding, the 16-byte chunk c of row r is stored in slot c ^ f(r), which makes both the
@@ -88,9 +89,10 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
     const int r = mm / g, j = mm - r * g;
     my_pos[b] = valid[b] ? q_pos[r] : -1;
     q_off[b] = ((long)r * n_q_heads + kvh * g + j) * DH;
+    const long q_src = ((long)(q_rows ? q_rows[r] : r) * n_q_heads + kvh * g + j) * DH;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-      qf[b][ks] = *reinterpret_cast<const bf16x8 *>(q + q_off[b] + ks * 16 + 8 * h);
+      qf[b][ks] = *reinterpret_cast<const bf16x8 *>(q + q_src + ks * 16 + 8 * h);
     wave_max_pos = max(wave_max_pos, my_pos[b]);
     wave_min_pos = min(wave_min_pos, my_pos[b]);       // invalid queries (-1) force masking
   }
@@ -349,7 +351,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
                                                        const int32_t *__restrict__ q_pos, int n_rows,
                                                        const float *__restrict__ kc,
                                                        const float *__restrict__ vc, float *__restrict__ o,
-                                                       int n_q_heads, int n_kv_heads, float scale_log2e) {
+                                                       int n_q_heads, int n_kv_heads, float scale_log2e,
+                                                       const int32_t *__restrict__ q_rows) {
   __shared__ float sq[4][DH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int idx = blockIdx.x * 4 + wave;
@@ -357,7 +360,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
   const int r = active ? idx / n_q_heads : 0, hq = active ? idx % n_q_heads : 0;
   const int kvh = hq / (n_q_heads / n_kv_heads);
   const int kv_dim = n_kv_heads * DH;
-  const float *qrow = q + ((size_t)r * n_q_heads + hq) * DH;
+  const float *qrow = q + ((size_t)(q_rows ? q_rows[r] : r) * n_q_heads + hq) * DH;
   for (int e = lane; e < DH; e += 64) sq[wave][e] = qrow[e];
   __syncthreads();
   if (!active) return;
@@ -425,7 +428,7 @@ size_t attention_partial_floats(int dtype, int n_rows, int hq, int hkv, int dh, 
   return (size_t)n_rows * hq * ns * (dh + 2);
 }
 
-hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int n_rows,
+hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, const int32_t *q_pos, int n_rows,
                             const void *kc, const void *vc, void *o, int hq, int hkv, int dh,
                             int n_tokens, float *partial, size_t partial_floats, hipStream_t s) {
   if (n_rows == 0) return hipSuccess;
@@ -434,10 +437,10 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int 
     dim3 grid((n_rows * hq + 3) / 4);
     if (dh == 64)
       hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, s, (const float *)q, q_pos, n_rows,
-                         (const float *)kc, (const float *)vc, (float *)o, hq, hkv, scale_log2e);
+                         (const float *)kc, (const float *)vc, (float *)o, hq, hkv, scale_log2e, q_rows);
     else
       hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(256), 0, s, (const float *)q, q_pos, n_rows,
-                         (const float *)kc, (const float *)vc, (float *)o, hq, hkv, scale_log2e);
+                         (const float *)kc, (const float *)vc, (float *)o, hq, hkv, scale_log2e, q_rows);
     return hipGetLastError();
   }
   const int g = hq / hkv;
@@ -463,7 +466,7 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int 
     hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_, NW_>),                                          \
                        dim3((unsigned)((n_flat + wgq - 1) / wgq), hkv, n_splits), dim3(64 * NW_),   \
                        smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc, (const bf16 *)vc, \
-                       (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml);              \
+                       (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml, q_rows);      \
   } while (0)
   if (dh == 64) CB_ATTN(64, 1, ATT_NW);
   else CB_ATTN(128, 1, ATT_NW);

@@ -77,12 +77,13 @@ hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s);
 
 // ---- attention.hip ---------------------------------------------------------
 // o[r, h, :] = softmax_{j <= q_pos[r]}(q[r,h,:] . K[j, h/g, :] / sqrt(dh)) V[j, h/g, :]
-// q, o: [n_rows, Hq, dh] storage type; caches [*, Hkv, dh]; q_pos ascending.
+// o: [n_rows, Hq, dh] storage type; q: row r is read at q[q_rows[r]] (q_rows NULL: q[r]);
+// caches [*, Hkv, dh]; q_pos ascending.
 // n_tokens: rows of the caches (upper bound of q_pos + 1).  partial: scratch for the KV split
 // used when there are few query rows (attention_partial_floats floats; NULL or too small: no split).
 size_t attention_partial_floats(int dtype, int n_rows, int n_q_heads, int n_kv_heads, int head_dim,
                                 int n_tokens);
-hipError_t launch_attention(int dtype, const void *q, const int32_t *q_pos, int n_rows,
+hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, const int32_t *q_pos, int n_rows,
                             const void *k_cache, const void *v_cache, void *o, int n_q_heads,
                             int n_kv_heads, int head_dim, int n_tokens, float *partial,
                             size_t partial_floats, hipStream_t s);
