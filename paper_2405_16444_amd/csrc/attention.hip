@@ -62,7 +62,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
   const int g = n_q_heads / n_kv_heads;
   const int kvh = blockIdx.y;
   const int n_flat = n_rows * g;
-  const int m_wg = blockIdx.x * WGQ;
+  // workgroups with the longest key range (the last rows) are dispatched first
+  const int m_wg = (int)(gridDim.x - 1 - blockIdx.x) * WGQ;
   const int kv_dim = n_kv_heads * DH;
 
   // causal bound of the workgroup = position of its last valid row
@@ -404,17 +405,23 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 // on the VALU while the other feeds the matrix core, and neither needs more than 256 registers).
 constexpr int ATT_NW = 8, ATT_WGQ = 32 * ATT_NW;
 
-// Split plan of the bf16 kernel: few query workgroups (the selective layers) leave most CUs
-// idle, so the key range is cut into n_splits pieces handled by separate workgroups.
-static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *n_splits, int *split_tiles) {
+// Split plan of the bf16 kernel.  Few query workgroups (the selective layers) leave most CUs idle,
+// so the key range is cut into pieces of split_tiles tiles handled by separate workgroups
+// (workgroup z takes tiles [z*split_tiles, (z+1)*split_tiles) and exits when its own causal
+// range ends before that).  Measured on 359..986-row layers: about one round of 256 workgroups
+// in total is the optimum; more pieces cost more in partial results than they gain in balance.
+static void attn_split_plan(int n_rows, int hq, int hkv, int dh, int n_tokens, int *n_splits, int *split_tiles) {
+  (void)dh;
   const long n_flat = (long)n_rows * (hq / hkv);
   const long base = ((n_flat + ATT_WGQ - 1) / ATT_WGQ) * hkv;
   const int max_tiles = (n_tokens + BKV - 1) / BKV;
   int ns = 1;
-  if (base < 384) {
-    ns = (int)((768 + base - 1) / base);
+  if (base < 128) {
+    ns = (int)((256 + base - 1) / base);
     ns = std::min(ns, std::max(1, max_tiles / 4));
     ns = std::min(ns, 32);
+  } else if (base < 256) {
+    ns = std::min(2, std::max(1, max_tiles / 4));
   }
   *split_tiles = (max_tiles + ns - 1) / ns;
   *n_splits = (max_tiles + *split_tiles - 1) / *split_tiles;
@@ -423,7 +430,7 @@ static void attn_split_plan(int n_rows, int hq, int hkv, int n_tokens, int *n_sp
 size_t attention_partial_floats(int dtype, int n_rows, int hq, int hkv, int dh, int n_tokens) {
   if (dtype == 0 || n_rows == 0) return 0;
   int ns, st;
-  attn_split_plan(n_rows, hq, hkv, n_tokens, &ns, &st);
+  attn_split_plan(n_rows, hq, hkv, dh, n_tokens, &ns, &st);
   if (ns <= 1) return 0;
   return (size_t)n_rows * hq * ns * (dh + 2);
 }
@@ -446,7 +453,7 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
   const int g = hq / hkv;
   const long n_flat = (long)n_rows * g;
   int n_splits, split_tiles;
-  attn_split_plan(n_rows, hq, hkv, n_tokens, &n_splits, &split_tiles);
+  attn_split_plan(n_rows, hq, hkv, dh, n_tokens, &n_splits, &split_tiles);
   if (n_splits > 1 && (!partial || partial_floats < (size_t)n_rows * hq * n_splits * (dh + 2))) {
     n_splits = 1;                                    // no scratch: one workgroup walks all keys
     split_tiles = (n_tokens + BKV - 1) / BKV;
