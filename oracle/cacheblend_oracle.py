@@ -31,6 +31,11 @@ because layer-0 K/V depend on the token alone; selection happens right after the
 K/V projection ("early filter"); ties go to the lower position; suffix (query)
 tokens are always kept and never candidates.
 
+Beyond the fusing path: the first-token head (final norm + vocabulary
+projection + greedy pick of the last query token: what "time to first token"
+ends with, Sec. 2) and the loading controller's delay estimators and choices
+(Sec. 5.1 and its two footnotes).
+
 Pinned by tests/test_oracle_*.py.  Unpinned readings: the deviation norm, the
 early-filter order, the ratio schedule and the rounding of k (the paper gives
 nothing to check them against) -- "parity unpinned" for those choices only.
@@ -350,3 +355,61 @@ def fuse_prefill(x, layers, m, chunk_lens, n_suffix, k_pre, v_pre, keep_counts,
         out.rows.append(len(pos))
     out.final_hidden = h[len(pos) - n_suffix:]
     return out
+
+
+# --------------------------------------------------------------------------- #
+# first token (Sec. 2: the prefill phase ends when the first token is generated)
+# --------------------------------------------------------------------------- #
+def first_token(final_hidden, norm_gain, lm_head, eps):
+    """Logits of the token that follows the last query token, and the greedy pick.
+
+    final_hidden [n_suffix, d] residual stream after the last layer; norm_gain
+    [d]; lm_head [vocab, d].  Returns (logits [vocab], token) with token the
+    smallest index among the largest logits.
+    """
+    x = rms_norm(np.asarray(final_hidden, F64)[-1], norm_gain, eps)
+    logits = np.asarray(lm_head, F64) @ x
+    return logits, arg_max_first(logits)
+
+
+def arg_max_first(values):
+    """Index of the largest entry; equal entries resolved towards the smaller index."""
+    values = np.asarray(values)
+    best = 0
+    for i in range(1, values.shape[0]):
+        if values[i] > values[best]:
+            best = i
+    return best
+
+
+# --------------------------------------------------------------------------- #
+# loading controller (Sec. 5.1)
+# --------------------------------------------------------------------------- #
+def recompute_delay(ratio, prefill_delay):
+    """T_recompute(r, LLM, L) = r x Prefill(LLM, L)  (first footnote of Sec. 5.1);
+    prefill_delay is the profiled full-prefill delay in the caller's unit."""
+    return ratio * prefill_delay
+
+
+def load_delay(per_token_kv_bytes, n_tokens, throughput_bytes_per_s):
+    """T_load(LLM, L, device) = PerTokenKVSize(LLM) x L / Throughput(device), seconds
+    (second footnote of Sec. 5.1).  per_token_kv_bytes is for whatever unit of the
+    cache is loaded (one layer for the layer-by-layer pipeline)."""
+    return per_token_kv_bytes * n_tokens / throughput_bytes_per_s
+
+
+def pick_recompute_ratio(prefill_delay, loading_delay, min_ratio=0.15):
+    """The ratio at which recompute takes as long as loading, but never below the
+    minimal ratio that keeps quality (r* = 15 % in the paper) nor above 1."""
+    r_equal = loading_delay / prefill_delay
+    return min(1.0, max(min_ratio, r_equal))
+
+
+def pick_storage_device(recompute_delay_value, load_delays, costs):
+    """Index of the cheapest device whose loading delay the recompute delay hides
+    (T_recompute >= T_load); ties in cost go to the lower index; -1 if none."""
+    best = -1
+    for i, (t, c) in enumerate(zip(load_delays, costs)):
+        if t <= recompute_delay_value and (best < 0 or c < costs[best]):
+            best = i
+    return best
