@@ -152,10 +152,36 @@ int cb_fuse_prefill(cb_ctx *ctx, const cb_layer_weights *layers, const void *x,
                     float *final_hidden, int32_t *const *sel_dump, float *const *dev_dump,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* First token (Sec. 2: the prefill phase ends when the first token is generated):
+ * RMSNorm of the LAST row of final_hidden, vocabulary projection, greedy pick.
+ *   final_hidden : float [n_suffix, d] as cb_fuse_prefill leaves it, n_suffix >= 1
+ *   final_norm   : T [d] gain of the final RMSNorm (eps = desc.rms_eps)
+ *   lm_head      : T [vocab, d] row-major
+ *   logits       : float [vocab] (out)
+ *   token        : int32 [1] (out, device): smallest index among the largest logits
+ * Needs d_model % 8 == 0 and d_model <= 16384 (else CB_EUNSUPPORTED). */
+int cb_first_token(cb_ctx *ctx, const float *final_hidden, int32_t n_suffix, const void *final_norm,
+                   const void *lm_head, int32_t vocab, float *logits, int32_t *token, void *stream);
+
+/* Loading controller (Sec. 5.1).  Plain host arithmetic, no ctx, no device work.
+ * cb_recompute_delay: T_recompute = ratio x profiled full-prefill delay (first footnote).
+ * cb_load_delay     : T_load = per-token KV bytes x tokens / device throughput, in seconds
+ *                     (second footnote); non-positive throughput gives +infinity.
+ * cb_pick_recompute_ratio: the ratio at which recompute takes as long as loading, clamped
+ *                     to [min_ratio, 1] (min_ratio = the paper's quality floor r*, 0.15).
+ * cb_pick_storage_device: index of the cheapest of n devices whose loading delay does not
+ *                     exceed recompute_delay (ties -> lower index), -1 if there is none.
+ *                     load_delays, costs: HOST double[n]. */
+double cb_recompute_delay(double ratio, double prefill_delay);
+double cb_load_delay(double per_token_kv_bytes, double n_tokens, double throughput_bytes_per_s);
+double cb_pick_recompute_ratio(double prefill_delay, double load_delay, double min_ratio);
+int32_t cb_pick_storage_device(double recompute_delay, const double *load_delays, const double *costs,
+                               int32_t n);
+
 /* Per-kernel-class timing for benchmarks.  Classes: */
 enum { CB_PROF_GEMM = 0, CB_PROF_ATTN = 1, CB_PROF_REALIGN = 2, CB_PROF_DEV = 3,
        CB_PROF_TOPK = 4, CB_PROF_NORM = 5, CB_PROF_OTHER = 6, CB_PROF_REDUCE = 7,
-       CB_PROF_NCLASS = 8 };
+       CB_PROF_HEAD = 8, CB_PROF_NCLASS = 9 };
 /* enable != 0: every later launch on ctx is bracketed by a pair of HIP events on
  * its stream (this slows the pass a little; do not time whole calls meanwhile). */
 int cb_profile_enable(cb_ctx *ctx, int32_t enable);

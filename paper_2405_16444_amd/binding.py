@@ -14,7 +14,8 @@ import torch  # imported before the library so both share one HIP runtime
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcacheblend.so")
 
 CB_F32, CB_BF16 = 0, 1
-PROF_CLASSES = ("gemm", "attention", "realign", "deviation", "topk", "norm", "other", "splitk_reduce")
+PROF_CLASSES = ("gemm", "attention", "realign", "deviation", "topk", "norm", "other", "splitk_reduce",
+                "first_token")
 
 
 class CacheBlendError(RuntimeError):
@@ -59,6 +60,16 @@ def _load():
     lib.cb_fuse_prefill.argtypes = [vp, C.POINTER(_LayerWeights), vp, C.POINTER(i32), i32, i32,
                                     C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp,
                                     C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
+    lib.cb_first_token.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
+    dbl = C.c_double
+    lib.cb_recompute_delay.argtypes = [dbl, dbl]
+    lib.cb_recompute_delay.restype = dbl
+    lib.cb_load_delay.argtypes = [dbl, dbl, dbl]
+    lib.cb_load_delay.restype = dbl
+    lib.cb_pick_recompute_ratio.argtypes = [dbl, dbl, dbl]
+    lib.cb_pick_recompute_ratio.restype = dbl
+    lib.cb_pick_storage_device.argtypes = [dbl, C.POINTER(dbl), C.POINTER(dbl), i32]
+    lib.cb_pick_storage_device.restype = i32
     lib.cb_profile_enable.argtypes = [vp, i32]
     lib.cb_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64),
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -68,7 +79,8 @@ def _load():
 _lib = _load()
 EXPORTS = ("cb_create", "cb_destroy", "cb_strerror", "cb_layer_workspace_bytes",
            "cb_prefill_workspace_bytes", "cb_default_schedule", "cb_realign_rope", "cb_fuse_layer",
-           "cb_fuse_prefill", "cb_profile_enable", "cb_profile_read")
+           "cb_fuse_prefill", "cb_first_token", "cb_recompute_delay", "cb_load_delay",
+           "cb_pick_recompute_ratio", "cb_pick_storage_device", "cb_profile_enable", "cb_profile_read")
 
 
 def _check(status: int, where: str):
@@ -246,6 +258,37 @@ def cb_fuse_prefill(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: 
     out.workspace = workspace
     out.weight_structs = weight_structs
     return out
+
+
+def cb_first_token(ctx: Context, final_hidden: torch.Tensor, final_norm: torch.Tensor, lm_head: torch.Tensor,
+                   stream=None, logits: Optional[torch.Tensor] = None, token: Optional[torch.Tensor] = None):
+    """(logits float [vocab], token int32 [1]) for the last row of final_hidden."""
+    n_suffix, vocab = final_hidden.shape[0], lm_head.shape[0]
+    dev = final_hidden.device
+    if logits is None:
+        logits = torch.empty(vocab, dtype=torch.float32, device=dev)
+    if token is None:
+        token = torch.empty(1, dtype=torch.int32, device=dev)
+    _check(_lib.cb_first_token(ctx._h, _ptr(final_hidden), n_suffix, _ptr(final_norm), _ptr(lm_head), vocab,
+                               _ptr(logits), _ptr(token), _stream(stream)), "cb_first_token")
+    return logits, token
+
+
+def cb_recompute_delay(ratio: float, prefill_delay: float) -> float:
+    return _lib.cb_recompute_delay(ratio, prefill_delay)
+
+
+def cb_load_delay(per_token_kv_bytes: float, n_tokens: float, throughput_bytes_per_s: float) -> float:
+    return _lib.cb_load_delay(per_token_kv_bytes, n_tokens, throughput_bytes_per_s)
+
+
+def cb_pick_recompute_ratio(prefill_delay: float, load_delay: float, min_ratio: float = 0.15) -> float:
+    return _lib.cb_pick_recompute_ratio(prefill_delay, load_delay, min_ratio)
+
+
+def cb_pick_storage_device(recompute_delay: float, load_delays: Sequence[float], costs: Sequence[float]) -> int:
+    n = len(load_delays)
+    return _lib.cb_pick_storage_device(recompute_delay, (C.c_double * n)(*load_delays), (C.c_double * n)(*costs), n)
 
 
 def cb_profile_enable(ctx: Context, enable: bool):

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libcacheblend.so")
-SOURCES = ["elementwise.hip", "select.hip", "gemm.hip", "attention.hip", "api.hip"]
+SOURCES = ["elementwise.hip", "select.hip", "gemm.hip", "attention.hip", "head.hip", "api.hip"]
 # packed-fp32 VALU forms are disabled on purpose (they have misbehaved on the test machines)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -44,7 +44,7 @@ def build(verbose: bool = False) -> str:
         _run(cmd)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(5, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
     if verbose:

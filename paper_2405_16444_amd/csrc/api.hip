@@ -499,6 +499,49 @@ int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, co
   return CB_OK;
 }
 
+int cb_first_token(cb_ctx *c, const float *final_hidden, int32_t n_suffix, const void *final_norm,
+                   const void *lm_head, int32_t vocab, float *logits, int32_t *token, void *stream) {
+  if (!c || !final_hidden || !final_norm || !lm_head || !logits || !token) return CB_ENULL;
+  if (n_suffix < 1 || vocab < 1) return CB_EINVAL;
+  const int d = c->m.d_model;
+  if (d % 8 != 0 || d > 16384) return CB_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t es = esize(c);
+  {
+    ProfScope ps(c, s, CB_PROF_HEAD, 2.0 * vocab * d, (double)vocab * d * es + (double)vocab * 4);
+    CB_HIP(launch_lm_head(c->m.dtype, final_hidden + (size_t)(n_suffix - 1) * d, final_norm, lm_head, d, vocab,
+                          c->m.rms_eps, logits, s));
+  }
+  {
+    ProfScope ps(c, s, CB_PROF_HEAD, 0, (double)vocab * 4);
+    CB_HIP(launch_argmax(logits, vocab, token, s));
+  }
+  return CB_OK;
+}
+
+double cb_recompute_delay(double ratio, double prefill_delay) { return ratio * prefill_delay; }
+
+double cb_load_delay(double per_token_kv_bytes, double n_tokens, double throughput_bytes_per_s) {
+  if (!(throughput_bytes_per_s > 0.0)) return HUGE_VAL;
+  return per_token_kv_bytes * n_tokens / throughput_bytes_per_s;
+}
+
+double cb_pick_recompute_ratio(double prefill_delay, double load_delay, double min_ratio) {
+  double r = prefill_delay > 0.0 ? load_delay / prefill_delay : 1.0;
+  if (r < min_ratio) r = min_ratio;
+  if (r > 1.0) r = 1.0;
+  return r;
+}
+
+int32_t cb_pick_storage_device(double recompute_delay, const double *load_delays, const double *costs,
+                               int32_t n) {
+  if (!load_delays || !costs) return -1;
+  int32_t best = -1;
+  for (int32_t i = 0; i < n; ++i)
+    if (load_delays[i] <= recompute_delay && (best < 0 || costs[i] < costs[best])) best = i;
+  return best;
+}
+
 int cb_profile_enable(cb_ctx *c, int32_t enable) {
   if (!c) return CB_ENULL;
   c->profiling = enable != 0;

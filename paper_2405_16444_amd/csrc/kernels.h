@@ -88,4 +88,12 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
                             int n_kv_heads, int head_dim, int n_tokens, float *partial,
                             size_t partial_floats, hipStream_t s);
 
+// ---- head.hip ---------------------------------------------------------------
+// logits[v] = T(rmsnorm(h_row) * gain) . w[v, :], v < vocab; w row-major [vocab, d]; d % 8 == 0,
+// d <= 16384 (the normalised row is held in LDS).
+hipError_t launch_lm_head(int dtype, const float *h_row, const void *gain, const void *w, int d, int vocab,
+                          float eps, float *logits, hipStream_t s);
+// token[0] = smallest index among the largest of logits[0..n).
+hipError_t launch_argmax(const float *logits, int n, int32_t *token, hipStream_t s);
+
 }  // namespace cb

@@ -87,3 +87,21 @@ def test_product_path_never_imports_the_oracle():
                 assert "oracle" not in src.lower(), f
     src = open(os.path.join(ROOT, "oracle", "cacheblend_oracle.py")).read()
     assert "paper_2405_16444_amd" not in src and "ctypes" not in src
+
+
+def test_loading_controller_matches_oracle():
+    """Host arithmetic of Sec. 5.1 through the C ABI against the oracle's definitions."""
+    import itertools
+    import paper_2405_16444_amd as P
+    from oracle import cacheblend_oracle as O
+    for r, pf in itertools.product([0.0, 0.05, 0.15, 1.0], [0.5, 20.0, 3000.0]):
+        assert P.cb_recompute_delay(r, pf) == O.recompute_delay(r, pf)
+    for kv, n, bw in itertools.product([4096.0, 16384.0, 131072.0], [1, 3136, 32896], [4.8e9, 64e9]):
+        assert P.cb_load_delay(kv, n, bw) == O.load_delay(kv, n, bw)
+    assert P.cb_load_delay(1.0, 1.0, 0.0) == float("inf")
+    for pf, ld, rmin in itertools.product([1.0, 20.0, 46.7], [0.5, 4.0, 16.0, 100.0], [0.0, 0.15, 0.3]):
+        assert P.cb_pick_recompute_ratio(pf, ld, rmin) == O.pick_recompute_ratio(pf, ld, rmin)
+    cases = [(3.0, [0.5, 2.5, 16.0], [9.0, 3.0, 1.0]), (20.0, [0.5, 2.5, 16.0], [9.0, 3.0, 1.0]),
+             (0.1, [0.5, 2.5, 16.0], [9.0, 3.0, 1.0]), (3.0, [1.0, 1.0], [2.0, 2.0]), (1.0, [], [])]
+    for t, loads, costs in cases:
+        assert P.cb_pick_storage_device(t, loads, costs) == O.pick_storage_device(t, loads, costs)

@@ -24,6 +24,7 @@ class ModelShape:
     rms_eps: float = 1e-5
     rope_theta: float = 1e4
     dtype: str = "bf16"  # "f32" or "bf16": storage type of weights, inputs, caches
+    vocab: int = 32000   # rows of the vocabulary projection (first-token head only)
 
     @property
     def q_dim(self) -> int:
@@ -86,7 +87,7 @@ def _ragged_lengths(n_chunks: int, lo: int, hi: int, seed: int):
 TINY = ModelShape(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64,
                   d_ff=688, rms_eps=1e-5, rope_theta=1e4, dtype="f32")
 MISTRAL_7B = ModelShape(32, 4096, 32, 8, 128, 14336, 1e-5, 1e6, "bf16")
-YI_34B = ModelShape(60, 7168, 56, 8, 128, 20480, 1e-5, 5e6, "bf16")
+YI_34B = ModelShape(60, 7168, 56, 8, 128, 20480, 1e-5, 5e6, "bf16", 64000)
 LLAMA_70B = ModelShape(80, 8192, 64, 8, 128, 28672, 1e-5, 1e4, "bf16")
 
 WORKLOADS = {

@@ -51,6 +51,14 @@ def layer_weights(model: ModelShape, layer: int, seed: int, device="cpu"):
     return out
 
 
+def head_weights(model: ModelShape, seed: int, device="cpu"):
+    """Final norm gain (ones) and vocabulary projection [vocab, d] ~ N(0, 0.02^2)."""
+    dt = storage_dtype(model)
+    s = (seed * 1_000_003 + 977_777) % (2 ** 63 - 1)
+    return {"final_norm": torch.ones(model.d_model, dtype=dt, device=device),
+            "lm_head": _normal((model.vocab, model.d_model), WEIGHT_STD, s, device, dt)}
+
+
 def model_weights(model: ModelShape, seed: int, device="cpu"):
     return [layer_weights(model, l, seed, device) for l in range(model.n_layers)]
 
