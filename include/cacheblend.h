@@ -152,6 +152,26 @@ int cb_fuse_prefill(cb_ctx *ctx, const cb_layer_weights *layers, const void *x,
                     float *final_hidden, int32_t *const *sel_dump, float *const *dev_dump,
                     void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same pass with the pre-computed caches still in HOST memory (Sec. 5: pipelining KV
+ * loading and recompute).  The copies of all layers are queued on copy_stream at once, in layer
+ * order; on `stream`, layer l waits for its own copy only, is re-aligned and fused, so loading
+ * layer l+1.. overlaps the recompute of layer l.
+ *   k_host_layers, v_host_layers : HOST arrays [L] of HOST pointers to T [n_ctx, Hkv, dh], each
+ *                   chunk cached at positions 0..; pinned memory if the copies are to overlap
+ *   k_cache_layers, v_cache_layers : HOST arrays [L] of device pointers to
+ *                   T [n_ctx + n_suffix, Hkv, dh]; receive the loaded rows and end as the fused caches
+ *   stream, copy_stream : two different streams of the same (default) priority; copy_stream first
+ *                   waits for the work already queued on stream.  All work, copies included, has
+ *                   completed once `stream` has been synchronised.
+ * Other arguments, validation and results as cb_fuse_prefill (without forced selections and dumps).
+ * The host buffers must stay valid and unchanged until then. */
+int cb_fuse_prefill_pipelined(cb_ctx *ctx, const cb_layer_weights *layers, const void *x,
+                              const int32_t *chunk_lens, int32_t n_chunks, int32_t n_suffix,
+                              const void *const *k_host_layers, const void *const *v_host_layers,
+                              void *const *k_cache_layers, void *const *v_cache_layers,
+                              const int32_t *keep_counts, float *final_hidden, void *workspace,
+                              size_t workspace_bytes, void *stream, void *copy_stream);
+
 /* First token (Sec. 2: the prefill phase ends when the first token is generated):
  * RMSNorm of the LAST row of final_hidden, vocabulary projection, greedy pick.
  *   final_hidden : float [n_suffix, d] as cb_fuse_prefill leaves it, n_suffix >= 1

@@ -60,6 +60,9 @@ def _load():
     lib.cb_fuse_prefill.argtypes = [vp, C.POINTER(_LayerWeights), vp, C.POINTER(i32), i32, i32,
                                     C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp,
                                     C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
+    lib.cb_fuse_prefill_pipelined.argtypes = [vp, C.POINTER(_LayerWeights), vp, C.POINTER(i32), i32, i32,
+                                              C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
+                                              C.POINTER(i32), vp, vp, sz, vp, vp]
     lib.cb_first_token.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
     dbl = C.c_double
     lib.cb_recompute_delay.argtypes = [dbl, dbl]
@@ -79,7 +82,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("cb_create", "cb_destroy", "cb_strerror", "cb_layer_workspace_bytes",
            "cb_prefill_workspace_bytes", "cb_default_schedule", "cb_realign_rope", "cb_fuse_layer",
-           "cb_fuse_prefill", "cb_first_token", "cb_recompute_delay", "cb_load_delay",
+           "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_first_token", "cb_recompute_delay", "cb_load_delay",
            "cb_pick_recompute_ratio", "cb_pick_storage_device", "cb_profile_enable", "cb_profile_read")
 
 
@@ -255,6 +258,43 @@ def cb_fuse_prefill(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: 
                                 _i32_array(keep_counts), forced_arr, _ptr(out._final_buf), sel_arr,
                                 dev_arr, _ptr(workspace), workspace.numel(), _stream(stream)),
            "cb_fuse_prefill")
+    out.workspace = workspace
+    out.weight_structs = weight_structs
+    return out
+
+
+def cb_fuse_prefill_pipelined(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: torch.Tensor,
+                              chunk_lens: Sequence[int], n_suffix: int, k_host_layers: Sequence[torch.Tensor],
+                              v_host_layers: Sequence[torch.Tensor], k_cache_layers: Sequence[torch.Tensor],
+                              v_cache_layers: Sequence[torch.Tensor], keep_counts: Sequence[int], copy_stream,
+                              workspace: Optional[torch.Tensor] = None, stream=None, weight_structs=None,
+                              out: Optional[SimpleNamespace] = None):
+    """cb_fuse_prefill with the pre-computed caches in (pinned) host tensors [n_ctx, Hkv, dh];
+    copy_stream: a torch.cuda.Stream of default priority, different from `stream`."""
+    dev_ = ctx.device
+    L, d = ctx.model.n_layers, ctx.model.d_model
+    n_ctx = int(sum(chunk_lens))
+    T = n_ctx + n_suffix
+    assert len(layers) == L and len(k_cache_layers) == L and len(v_cache_layers) == L and len(keep_counts) == L
+    assert len(k_host_layers) == L and len(v_host_layers) == L
+    assert x.dtype == ctx.dtype and x.shape == (T, d) and x.is_contiguous()
+    for t in list(k_cache_layers) + list(v_cache_layers):
+        assert t.dtype == ctx.dtype and t.is_contiguous() and t.shape[0] == T and t.is_cuda
+    for t in list(k_host_layers) + list(v_host_layers):
+        assert t.dtype == ctx.dtype and t.is_contiguous() and t.shape[0] == n_ctx and not t.is_cuda
+    if weight_structs is None:
+        weight_structs = (_LayerWeights * L)(*[_weights_struct(lw, ctx.dtype, dev_) for lw in layers])
+    if out is None:
+        out = SimpleNamespace()
+        out._final_buf = torch.empty((max(1, n_suffix), d), dtype=torch.float32, device=dev_)
+        out.final_hidden = out._final_buf[:n_suffix]
+    if workspace is None:
+        workspace = torch.empty(cb_prefill_workspace_bytes(ctx, T), dtype=torch.uint8, device=dev_)
+    _check(_lib.cb_fuse_prefill_pipelined(
+        ctx._h, weight_structs, _ptr(x), _i32_array(chunk_lens), len(chunk_lens), n_suffix,
+        _ptr_array(k_host_layers), _ptr_array(v_host_layers), _ptr_array(k_cache_layers),
+        _ptr_array(v_cache_layers), _i32_array(keep_counts), _ptr(out._final_buf), _ptr(workspace),
+        workspace.numel(), _stream(stream), _stream(copy_stream)), "cb_fuse_prefill_pipelined")
     out.workspace = workspace
     out.weight_structs = weight_structs
     return out

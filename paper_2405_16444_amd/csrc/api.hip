@@ -33,6 +33,7 @@ struct cb_ctx {
   bool profiling;
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> free_events;
+  std::vector<hipEvent_t> load_events;   // pipelined loading: [0] = entry fence, [1 + l] = layer l landed
 };
 
 namespace {
@@ -357,6 +358,7 @@ void cb_destroy(cb_ctx *c) {
   if (!c) return;
   for (auto &r : c->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
   for (auto e : c->free_events) (void)hipEventDestroy(e);
+  for (auto e : c->load_events) (void)hipEventDestroy(e);
   if (c->rope_tab) (void)hipFree(c->rope_tab);
   delete c;
 }
@@ -432,11 +434,18 @@ int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const flo
                          h_out, pos_out, dev_out, ws, (hipStream_t)stream);
 }
 
-int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, const int32_t *chunk_lens,
-                    int32_t n_chunks, int32_t n_suffix, void *const *k_cache_layers,
-                    void *const *v_cache_layers, const int32_t *keep_counts,
-                    const int32_t *const *forced_sel, float *final_hidden, int32_t *const *sel_dump,
-                    float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) {
+namespace {
+
+// Body of cb_fuse_prefill and cb_fuse_prefill_pipelined.  k_host/v_host NULL: the caches are
+// already on the device and all layers are re-aligned in one launch.  Otherwise layer l's rows
+// are copied from host memory on copy_stream, and the compute stream waits for that copy,
+// re-aligns the layer and fuses it (Sec. 5, pipelining of loading and recompute).
+int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const int32_t *chunk_lens,
+                 int32_t n_chunks, int32_t n_suffix, const void *const *k_host, const void *const *v_host,
+                 void *const *k_cache_layers, void *const *v_cache_layers, const int32_t *keep_counts,
+                 const int32_t *const *forced_sel, float *final_hidden, int32_t *const *sel_dump,
+                 float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream,
+                 void *copy_stream) {
   if (!c || !layers || !x || !chunk_lens || !k_cache_layers || !v_cache_layers || !keep_counts ||
       !workspace)
     return CB_ENULL;
@@ -457,10 +466,29 @@ int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, co
     if (keep_counts[l] < 0 || keep_counts[l] > keep_counts[l - 1]) return CB_EINVAL;
   for (int l = 0; l < L; ++l) {
     if (!k_cache_layers[l] || !v_cache_layers[l]) return CB_ENULL;
+    if (k_host && (!k_host[l] || !v_host[l])) return CB_ENULL;
     int st = check_layer_args(c, l, &layers[l], T, n_suffix, T, 0);
     if (st != CB_OK) return st;
   }
   if (cb_prefill_workspace_bytes(c, T) > workspace_bytes) return CB_EWORKSPACE;
+  if (k_host) {
+    // the copies of every layer are queued now; the copy stream first waits for whatever the
+    // compute stream still has in flight on the destination buffers
+    while ((int)c->load_events.size() < L + 1) {
+      hipEvent_t e = nullptr;
+      CB_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      c->load_events.push_back(e);
+    }
+    hipStream_t cs = (hipStream_t)copy_stream;
+    CB_HIP(hipEventRecord(c->load_events[0], (hipStream_t)stream));
+    CB_HIP(hipStreamWaitEvent(cs, c->load_events[0], 0));
+    const size_t bytes = (size_t)C * c->m.n_kv_heads * c->m.head_dim * esize(c);
+    for (int l = 0; l < L; ++l) {
+      CB_HIP(hipMemcpyAsync(k_cache_layers[l], k_host[l], bytes, hipMemcpyHostToDevice, cs));
+      CB_HIP(hipMemcpyAsync(v_cache_layers[l], v_host[l], bytes, hipMemcpyHostToDevice, cs));
+      CB_HIP(hipEventRecord(c->load_events[1 + l], cs));
+    }
+  }
 
   hipStream_t s = (hipStream_t)stream;
   char *base = (char *)workspace;
@@ -475,12 +503,20 @@ int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, co
     hipLaunchKernelGGL(iota_kernel, dim3((T + 255) / 256), dim3(256), 0, s, p_cur, T);
     CB_HIP(hipGetLastError());
   }
-  int st = cb_realign_rope(c, k_cache_layers, 0, L, off.data(), n_chunks, stream);
-  if (st != CB_OK) return st;
+  int st = CB_OK;
+  if (!k_host) {
+    st = cb_realign_rope(c, k_cache_layers, 0, L, off.data(), n_chunks, stream);
+    if (st != CB_OK) return st;
+  }
 
   int n = T;
   for (int l = 0; l < L; ++l) {
     const int k = keep_counts[l];
+    if (k_host) {
+      CB_HIP(hipStreamWaitEvent(s, c->load_events[1 + l], 0));
+      st = cb_realign_rope(c, k_cache_layers, l, l + 1, off.data(), n_chunks, stream);
+      if (st != CB_OK) return st;
+    }
     const int32_t *forced = forced_sel ? forced_sel[l] : nullptr;
     float *dev_out = dev_dump ? dev_dump[l] : nullptr;
     st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, n, n_suffix, k_cache_layers[l], v_cache_layers[l],
@@ -497,6 +533,31 @@ int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, co
     CB_HIP(launch_copy_rows_f32(h_cur + (size_t)(n - n_suffix) * d, final_hidden, (size_t)n_suffix * d, s));
   }
   return CB_OK;
+}
+
+}  // namespace
+
+int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, const int32_t *chunk_lens,
+                    int32_t n_chunks, int32_t n_suffix, void *const *k_cache_layers,
+                    void *const *v_cache_layers, const int32_t *keep_counts,
+                    const int32_t *const *forced_sel, float *final_hidden, int32_t *const *sel_dump,
+                    float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) {
+  return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, nullptr, nullptr, k_cache_layers,
+                      v_cache_layers, keep_counts, forced_sel, final_hidden, sel_dump, dev_dump, workspace,
+                      workspace_bytes, stream, nullptr);
+}
+
+int cb_fuse_prefill_pipelined(cb_ctx *c, const cb_layer_weights *layers, const void *x,
+                              const int32_t *chunk_lens, int32_t n_chunks, int32_t n_suffix,
+                              const void *const *k_host_layers, const void *const *v_host_layers,
+                              void *const *k_cache_layers, void *const *v_cache_layers,
+                              const int32_t *keep_counts, float *final_hidden, void *workspace,
+                              size_t workspace_bytes, void *stream, void *copy_stream) {
+  if (!k_host_layers || !v_host_layers) return CB_ENULL;
+  if (stream == copy_stream) return CB_EINVAL;       // the copies must not queue behind the compute
+  return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, k_host_layers, v_host_layers,
+                      k_cache_layers, v_cache_layers, keep_counts, nullptr, final_hidden, nullptr, nullptr,
+                      workspace, workspace_bytes, stream, copy_stream);
 }
 
 int cb_first_token(cb_ctx *c, const float *final_hidden, int32_t n_suffix, const void *final_norm,
