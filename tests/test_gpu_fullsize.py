@@ -65,6 +65,7 @@ def run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, want_dev):
 
 
 @pytest.mark.parametrize("name,n_tokens,n_rows,n_suffix,k_keep", [
+    ("mistral7b", 3136, 3136, 64, 922),       # layer 1: first check on all 3072 context rows, Q projected after the selection
     ("mistral7b", 3136, 986, 64, 877),        # layer 2 of the gradual schedule: check on 922 candidates
     ("mistral7b", 3136, 359, 64, 231),        # last layer: 295 candidates -> 231
     ("mistral7b", 3136, 589, 64, 461),        # 525 rows kept (flat 15 %): the gate/up GEMM's last round of tiles is shared along K
