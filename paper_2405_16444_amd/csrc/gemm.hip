@@ -164,8 +164,8 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //               explicit waits; plain s_barrier is used because __syncthreads()
 //               would drain every outstanding load.
 //   tile order  1-D grid; workgroup id -> (xcd = id % 8, j = id / 8); an XCD walks
-//               its own n-tiles (n % 8 == xcd) with the m-tiles innermost, so the
-//               workgroups that share a weight tile run back to back on one L2.
+//               its own n-tiles (n % 8 == xcd) in groups of 8 m-tiles (xcd_tile), so the
+//               workgroups that share a weight or activation tile run together on one L2.
 // Requires K % 64 == 0 and k_per_split % 64 == 0.
 // ---------------------------------------------------------------------------
 constexpr int DMA_BK = 64;
@@ -197,6 +197,22 @@ template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_wa
 __device__ __forceinline__ void lds_pin(bf16x8 &f) { asm volatile("" : "+v"(f)); }
 template <int N> __device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Tile walked by the j-th workgroup of an XCD (j < nblk * tiles_m).  The XCD owns the n-tiles
+// congruent to its index mod 8 (nblk of them); row tiles are taken in groups of 8 and, inside a
+// group, the row tiles of one n-tile come first.  The ~32 workgroups resident on an XCD then
+// cover about 4 n-tiles x 8 m-tiles, so every weight tile and every activation tile fetched into
+// its L2 serves several of them (with all row tiles innermost, a problem with many row tiles
+// would share no activation tile at all).
+constexpr int kGroupM = 8;
+__device__ __forceinline__ void xcd_tile(int j, int xcd, int tiles_m, int nblk, int *nt, int *mt) {
+  const int per_group = nblk * kGroupM, full = tiles_m / kGroupM;
+  int g = j / per_group, r, gm;
+  if (g >= full) { g = full; r = j - full * per_group; gm = tiles_m - full * kGroupM; }
+  else { r = j - g * per_group; gm = kGroupM; }
+  *nt = xcd + 8 * (r / gm);
+  *mt = g * kGroupM + r % gm;
+}
 
 // silu(gate) * up from one wavefront's accumulators of a (32*I) x (64*NB) tile: blocks
 // 0..NB/2-1 of a lane hold gate columns, blocks NB/2..NB-1 the same columns of the up matrix;
@@ -239,7 +255,8 @@ __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tile
   const int u = (blockIdx.x % (UNITS / 4)) * 4 + (threadIdx.x >> 6);
   const int wave = u / (IH * HB), i = (u / HB) % IH, jb = u % HB;
   const int xcd = slot & 7, j = (p.tail_first >> 3) + (slot >> 3);
-  const int nt = xcd + 8 * (j / tiles_m), mt = j % tiles_m;
+  int nt, mt;
+  xcd_tile(j, xcd, tiles_m, (tiles_n + 7) >> 3, &nt, &mt);
   if (nt >= tiles_n) return;
   const float *pg = p.partial + (size_t)slot * p.tail_splits * (BM * BN) + (size_t)wave * (IH * NB * 16 * 64) +
                     (size_t)(i * NB + jb) * (16 * 64) + lane;
@@ -288,7 +305,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   const int nblk = (tiles_n + 7) >> 3;
   const int per_z = nblk * tiles_m;
   const int z = j / per_z, rem = j - z * per_z;
-  const int nt = xcd + 8 * (rem / tiles_m), mt = rem % tiles_m;
+  int nt, mt;
+  xcd_tile(rem, xcd, tiles_m, nblk, &nt, &mt);
   if (nt >= tiles_n) return;
   const int m0 = mt * BM, n0 = nt * OUT_COLS;
   const int kps = tail_z >= 0 ? p.tail_k_per_split : p.k_per_split;
