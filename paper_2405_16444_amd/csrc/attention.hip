@@ -60,10 +60,10 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, h = lane >> 5;
   const int g = n_q_heads / n_kv_heads;
-  const int kvh = blockIdx.y;
+  const int kvh = blockIdx.x;                          // kv head varies fastest in dispatch order
   const int n_flat = n_rows * g;
-  // workgroups with the longest key range (the last rows) are dispatched first
-  const int m_wg = (int)(gridDim.x - 1 - blockIdx.x) * WGQ;
+  // workgroups with the longest key range (the last rows) are dispatched first, for every kv head
+  const int m_wg = (int)(gridDim.y - 1 - blockIdx.y) * WGQ;
   const int kv_dim = n_kv_heads * DH;
 
   // causal bound of the workgroup = position of its last valid row
@@ -471,7 +471,7 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
       attr_set = true;                                                                              \
     }                                                                                               \
     hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_, NW_>),                                          \
-                       dim3((unsigned)((n_flat + wgq - 1) / wgq), hkv, n_splits), dim3(64 * NW_),   \
+                       dim3(hkv, (unsigned)((n_flat + wgq - 1) / wgq), n_splits), dim3(64 * NW_),   \
                        smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc, (const bf16 *)vc, \
                        (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml, q_rows);      \
   } while (0)
