@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--flat", action="store_true", help="flat schedule instead of gradual filtering")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="requests fused per call (cb_fuse_prefill_batched when > 1; distinct inputs per request)")
     ap.add_argument("--no-host-load", action="store_true",
                     help="skip the variant that loads the chunk caches from pinned host memory")
     return ap.parse_args()
@@ -92,6 +94,80 @@ def cpu_baseline(w, keep):
                       f"{dt_s:.1f} s"}
 
 
+def bench_batched(a, w, keep, P, producer, synth, torch, np):
+    """B requests of the workload's shape (own inputs each) fused by one cb_fuse_prefill_batched call."""
+    from dataclasses import replace
+    m, B = w.model, a.batch
+    dev = torch.device("cuda:0")
+    L, C, S, T = m.n_layers, w.n_ctx, w.n_suffix, w.n_tokens
+    layers = [synth.layer_weights(m, l, w.seed_weights, device=dev) for l in range(L)]
+    ctx = P.cb_create(m, T)
+    xs, k_pre, v_pre = [], [[] for _ in range(L)], [[] for _ in range(L)]
+    for b in range(B):
+        xb = synth.hidden_inputs(replace(w, seed_inputs=w.seed_inputs + 101 * b), device=dev)
+        kb, vb = producer.chunk_prefill(ctx, layers, xb[:C], w.chunk_lens, T)
+        xs.append(xb)
+        for l in range(L):
+            k_pre[l].append(kb[l])
+            v_pre[l].append(vb[l])
+    x = torch.cat(xs).contiguous()
+    k_pre = [torch.cat(t).contiguous() for t in k_pre]          # [B * T, Hkv, dh], slabs T rows apart
+    v_pre = [torch.cat(t).contiguous() for t in v_pre]
+    torch.cuda.synchronize()
+    k_work = [t.clone() for t in k_pre]
+    v_work = [t.clone() for t in v_pre]
+
+    def restore():
+        for dst, src in zip(k_work + v_work, k_pre + v_pre):
+            dst.copy_(src)
+
+    out = None
+
+    def step():
+        nonlocal out
+        out = P.cb_fuse_prefill_batched(ctx, layers, x, [w.chunk_lens] * B, [S] * B, k_work, v_work, T, [keep] * B,
+                                        workspace=None if out is None else out.workspace,
+                                        weight_structs=None if out is None else out.weight_structs, out=out)
+
+    for _ in range(max(1, a.warmup)):
+        restore()
+        step()
+    torch.cuda.synchronize()
+    wall = []
+    for _ in range(a.steps):
+        restore()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        wall.append((time.perf_counter() - t0) * 1e3)
+    ms = float(np.mean(wall))
+    P.cb_profile_enable(ctx, True)
+    restore()
+    step()
+    torch.cuda.synchronize()
+    prof = P.cb_profile_read(ctx)
+    P.cb_profile_enable(ctx, False)
+    g = prof["gemm"]
+    achieved = g["flops"] / g["ms"] / 1e9
+    token_layers = float(B * sum(k + S for k in keep))
+    P.cb_destroy(ctx)
+    print(json.dumps({
+        "metric": "hkvd_recompute_tokens_per_s (token-layers recomputed per second over one fused prefill)",
+        "value": token_layers / (ms * 1e-3), "unit": "token-layers/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms, "ms_per_request": ms / B, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "layers": L, "n_ctx": C, "n_suffix": S, "ratio": w.ratio,
+                   "schedule": "flat" if a.flat else "gradual", "token_layers": token_layers},
+        "roofline": {"kernel": "gemm_bf16_dma_kernel (all epilogues)", "bound": "mfma", "achieved": achieved,
+                     "peak": PEAK["mfma_bf16_tflops"], "unit": "TFLOP/s", "frac": achieved / PEAK["mfma_bf16_tflops"],
+                     "traffic": None},
+        "cpu_baseline": None,
+        "kernel_classes": {c: {"ms_per_step": v["ms"], "launches_per_step": v["launches"]} for c, v in prof.items()
+                           if v["launches"]},
+    }))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -116,6 +192,9 @@ def main():
     torch.cuda.set_device(dev)
     L, C, S, T = m.n_layers, w.n_ctx, w.n_suffix, w.n_tokens
     keep = P.cb_default_schedule(L, C, w.ratio, w.ratio_first, a.flat)
+
+    if a.batch > 1:
+        return bench_batched(a, w, keep, P, producer, synth, torch, np)
 
     # ---- setup (untimed): weights, inputs, pre-computed chunk caches ----
     layers = [synth.layer_weights(m, l, w.seed_weights, device=dev) for l in range(L)]

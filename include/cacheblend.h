@@ -172,6 +172,30 @@ int cb_fuse_prefill_pipelined(cb_ctx *ctx, const cb_layer_weights *layers, const
                               const int32_t *keep_counts, float *final_hidden, void *workspace,
                               size_t workspace_bytes, void *stream, void *copy_stream);
 
+/* Several requests in one pass (Sec. 7 sensitivity analysis, "varying batch size"): the projections and the MLP run on
+ * the stacked rows of all requests, selection and attention per request.  Request b contributes
+ * n_chunks[b] chunks and n_suffix[b] query tokens; T_b = its context + suffix length.
+ *   x             : T [sum_b T_b, d], request after request, each: context chunks then suffix
+ *   chunk_lens    : HOST int32[sum_b n_chunks[b]], the requests' chunk lengths one after another
+ *   n_chunks, n_suffix : HOST int32[n_requests]
+ *   k_cache_layers, v_cache_layers : HOST arrays [L] of device pointers to
+ *                   T [n_requests * cache_stride, Hkv, dh]; request b owns rows
+ *                   [b * cache_stride, b * cache_stride + T_b), laid out as for cb_fuse_prefill
+ *   cache_stride  : rows between two requests' slabs, >= max_b T_b
+ *   keep_counts   : HOST int32[n_requests * L], keep_counts[b * L + l]; per request as in cb_fuse_prefill
+ *   final_hidden  : float [sum_b n_suffix[b], d], request after request
+ *   sel_dump      : NULL, or HOST array [n_requests * L] of (NULL | device int32[keep_counts[b * L + l]])
+ *   dev_dump      : NULL, or HOST array [L] of (NULL | device float[rows entering layer l]): the
+ *                   deviation of every stacked row in row order (values at suffix rows are meaningless)
+ * Each request's results equal those of its own cb_fuse_prefill call up to the summation order of
+ * the projections. */
+size_t cb_batched_workspace_bytes(const cb_ctx *ctx, int32_t total_tokens);
+int cb_fuse_prefill_batched(cb_ctx *ctx, const cb_layer_weights *layers, int32_t n_requests, const void *x,
+                            const int32_t *chunk_lens, const int32_t *n_chunks, const int32_t *n_suffix,
+                            void *const *k_cache_layers, void *const *v_cache_layers, int32_t cache_stride,
+                            const int32_t *keep_counts, float *final_hidden, int32_t *const *sel_dump,
+                            float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream);
+
 /* First token (Sec. 2: the prefill phase ends when the first token is generated):
  * RMSNorm of the LAST row of final_hidden, vocabulary projection, greedy pick.
  *   final_hidden : float [n_suffix, d] as cb_fuse_prefill leaves it, n_suffix >= 1

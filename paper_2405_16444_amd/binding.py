@@ -63,6 +63,11 @@ def _load():
     lib.cb_fuse_prefill_pipelined.argtypes = [vp, C.POINTER(_LayerWeights), vp, C.POINTER(i32), i32, i32,
                                               C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp),
                                               C.POINTER(i32), vp, vp, sz, vp, vp]
+    lib.cb_batched_workspace_bytes.argtypes = [vp, i32]
+    lib.cb_batched_workspace_bytes.restype = sz
+    lib.cb_fuse_prefill_batched.argtypes = [vp, C.POINTER(_LayerWeights), i32, vp, C.POINTER(i32), C.POINTER(i32),
+                                            C.POINTER(i32), C.POINTER(vp), C.POINTER(vp), i32, C.POINTER(i32),
+                                            vp, C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
     lib.cb_first_token.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
     dbl = C.c_double
     lib.cb_recompute_delay.argtypes = [dbl, dbl]
@@ -82,7 +87,8 @@ def _load():
 _lib = _load()
 EXPORTS = ("cb_create", "cb_destroy", "cb_strerror", "cb_layer_workspace_bytes",
            "cb_prefill_workspace_bytes", "cb_default_schedule", "cb_realign_rope", "cb_fuse_layer",
-           "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_first_token", "cb_recompute_delay", "cb_load_delay",
+           "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_batched_workspace_bytes",
+           "cb_fuse_prefill_batched", "cb_first_token", "cb_recompute_delay", "cb_load_delay",
            "cb_pick_recompute_ratio", "cb_pick_storage_device", "cb_profile_enable", "cb_profile_read")
 
 
@@ -295,6 +301,59 @@ def cb_fuse_prefill_pipelined(ctx: Context, layers: Sequence[Dict[str, torch.Ten
         _ptr_array(k_host_layers), _ptr_array(v_host_layers), _ptr_array(k_cache_layers),
         _ptr_array(v_cache_layers), _i32_array(keep_counts), _ptr(out._final_buf), _ptr(workspace),
         workspace.numel(), _stream(stream), _stream(copy_stream)), "cb_fuse_prefill_pipelined")
+    out.workspace = workspace
+    out.weight_structs = weight_structs
+    return out
+
+
+def cb_batched_workspace_bytes(ctx: Context, total_tokens: int) -> int:
+    return int(_lib.cb_batched_workspace_bytes(ctx._h, total_tokens))
+
+
+def cb_fuse_prefill_batched(ctx: Context, layers: Sequence[Dict[str, torch.Tensor]], x: torch.Tensor,
+                            chunk_lens: Sequence[Sequence[int]], n_suffix: Sequence[int],
+                            k_cache_layers: Sequence[torch.Tensor], v_cache_layers: Sequence[torch.Tensor],
+                            cache_stride: int, keep_counts: Sequence[Sequence[int]], want_sel: bool = False,
+                            want_dev: bool = False, workspace: Optional[torch.Tensor] = None, stream=None,
+                            weight_structs=None, out: Optional[SimpleNamespace] = None):
+    """Several requests stacked in one call.  chunk_lens / n_suffix / keep_counts: one entry per
+    request; caches: per layer one tensor [n_requests * cache_stride, Hkv, dh].  Returns a namespace
+    with final_hidden [sum n_suffix, d], sel[b][l] and dev[l] (when asked for)."""
+    dev_ = ctx.device
+    B, L, d = len(chunk_lens), ctx.model.n_layers, ctx.model.d_model
+    T = [int(sum(cl)) + int(s) for cl, s in zip(chunk_lens, n_suffix)]
+    N, S_tot = sum(T), int(sum(n_suffix))
+    assert len(n_suffix) == B and len(keep_counts) == B and all(len(k) == L for k in keep_counts)
+    assert len(layers) == L and len(k_cache_layers) == L and len(v_cache_layers) == L
+    assert x.dtype == ctx.dtype and x.shape == (N, d) and x.is_contiguous()
+    for t in list(k_cache_layers) + list(v_cache_layers):
+        assert t.dtype == ctx.dtype and t.is_contiguous() and t.shape[0] == B * cache_stride
+    if weight_structs is None:
+        weight_structs = (_LayerWeights * L)(*[_weights_struct(lw, ctx.dtype, dev_) for lw in layers])
+    if out is None:
+        out = SimpleNamespace()
+        out._final_buf = torch.empty((max(1, S_tot), d), dtype=torch.float32, device=dev_)
+        out.final_hidden = out._final_buf[:S_tot]
+        out.sel = out.dev = None
+        if want_sel:
+            out._sel_buf = [torch.empty((max(1, int(k)),), dtype=torch.int32, device=dev_)
+                            for kc in keep_counts for k in kc]
+            out.sel = [[out._sel_buf[b * L + l][:int(keep_counts[b][l])] for l in range(L)] for b in range(B)]
+        if want_dev:
+            rows_in = [N] + [sum(int(keep_counts[b][l]) + int(n_suffix[b]) for b in range(B)) for l in range(L - 1)]
+            out._dev_buf = [torch.zeros((max(1, r),), dtype=torch.float32, device=dev_) for r in rows_in]
+            out.dev = [b_[:r] for b_, r in zip(out._dev_buf, rows_in)]
+    if workspace is None:
+        workspace = torch.empty(cb_batched_workspace_bytes(ctx, N), dtype=torch.uint8, device=dev_)
+    flat_chunks = [int(v) for cl in chunk_lens for v in cl]
+    flat_keep = [int(v) for kc in keep_counts for v in kc]
+    sel_arr = _ptr_array(out._sel_buf) if out.sel is not None else None
+    dev_arr = _ptr_array(out._dev_buf) if out.dev is not None else None
+    _check(_lib.cb_fuse_prefill_batched(
+        ctx._h, weight_structs, B, _ptr(x), _i32_array(flat_chunks), _i32_array([len(cl) for cl in chunk_lens]),
+        _i32_array(n_suffix), _ptr_array(k_cache_layers), _ptr_array(v_cache_layers), cache_stride,
+        _i32_array(flat_keep), _ptr(out._final_buf), sel_arr, dev_arr, _ptr(workspace), workspace.numel(),
+        _stream(stream)), "cb_fuse_prefill_batched")
     out.workspace = workspace
     out.weight_structs = weight_structs
     return out

@@ -127,9 +127,9 @@ LayerWs carve_layer(const cb_ctx *c, char *base, int R) {
   return w;
 }
 
-__global__ void iota_kernel(int32_t *p, int n) {
+__global__ void iota_kernel(int32_t *p, int n, int base) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = i;
+  if (i < n) p[i] = base + i;
 }
 
 #define CB_HIP(expr)                     \
@@ -151,18 +151,32 @@ int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int 
   return CB_OK;
 }
 
-// the layer body; arguments already validated
+// One request's share of the rows of a layer call: n rows enter (the last S of them its suffix),
+// k context rows are kept, its caches hold T rows.
+struct Seg { int n, S, k, T; };
+
+// The layer body; arguments already validated.  Rows of several requests may be stacked
+// (request-major): the projections then run on all of them at once, selection and attention per
+// request.  cache_row (NULL: row_pos) gives each row's row in the cache arrays, which hold the
+// requests' slabs cache_stride rows apart; cache_row_out receives it for the kept rows.
 int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, const int32_t *row_pos,
-                    int n, int S, void *kc, void *vc, int n_tokens, int k, const int32_t *forced, float *h_out,
-                    int32_t *pos_out, float *dev_out, const LayerWs &ws, hipStream_t s) {
+                    const int32_t *cache_row, const Seg *segs, int n_segs, size_t cache_stride, void *kc,
+                    void *vc, const int32_t *forced, float *h_out, int32_t *pos_out, int32_t *cache_row_out,
+                    float *dev_out, const LayerWs &ws, hipStream_t s) {
   const cb_model_desc &m = c->m;
   const int dt = m.dtype;
   const size_t es = esize(c);
   const int d = m.d_model, q_dim = m.n_q_heads * m.head_dim, kv_dim = m.n_kv_heads * m.head_dim;
   const int F = m.d_ff;
-  const int n_cand = n - S, rows = k + S;
-  const bool check = (k < n_cand) || forced != nullptr;
+  int n = 0, rows = 0;
+  bool check = forced != nullptr;
+  for (int b = 0; b < n_segs; ++b) {
+    n += segs[b].n;
+    rows += segs[b].k + segs[b].S;
+    check = check || segs[b].k < segs[b].n - segs[b].S;
+  }
   if (n == 0) return CB_OK;
+  const int32_t *crow = cache_row ? cache_row : row_pos;
 
   {
     ProfScope ps(c, s, CB_PROF_NORM, 0, (double)n * d * (4 + es));
@@ -196,21 +210,35 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       CB_HIP(launch_gemm_reduce(g, s));
     }
     float *dev = dev_out ? dev_out : ws.dev;
+    // one request: its candidates are the leading rows; several: every row gets a value (a
+    // suffix row's is never looked at)
+    const int n_dev = n_segs == 1 ? n - segs[0].S : n;
     {
-      ProfScope ps(c, s, CB_PROF_DEV, 4.0 * n_cand * 2 * kv_dim, (double)n_cand * (4.0 * kv_dim * es + 4));
-      CB_HIP(launch_deviation(dt, ws.kvnew, row_pos, n_cand, kc, vc, kv_dim, dev, s));
+      ProfScope ps(c, s, CB_PROF_DEV, 4.0 * n_dev * 2 * kv_dim, (double)n_dev * (4.0 * kv_dim * es + 4));
+      CB_HIP(launch_deviation(dt, ws.kvnew, crow, n_dev, kc, vc, kv_dim, dev, s));
     }
     {
-      ProfScope ps(c, s, CB_PROF_TOPK, 0, (double)n_cand * 4 + (double)rows * 8);
-      if (forced) CB_HIP(launch_forced_map(forced, k, row_pos, n_cand, S, ws.sel_rows, pos_out, s));
-      else CB_HIP(launch_topk(dev, n_cand, k, S, row_pos, ws.sel_rows, pos_out, s));
+      ProfScope ps(c, s, CB_PROF_TOPK, 0, (double)n_dev * 4 + (double)rows * 8);
+      if (forced) {
+        CB_HIP(launch_forced_map(forced, segs[0].k, row_pos, n - segs[0].S, segs[0].S, ws.sel_rows, pos_out, s));
+      } else {
+        int in_off = 0, out_off = 0;
+        for (int b = 0; b < n_segs; ++b) {
+          CB_HIP(launch_topk(dev + in_off, segs[b].n - segs[b].S, segs[b].k, segs[b].S, row_pos + in_off,
+                             ws.sel_rows + out_off, pos_out + out_off, in_off, s));
+          in_off += segs[b].n;
+          out_off += segs[b].k + segs[b].S;
+        }
+      }
+      if (cache_row_out && rows > 0) CB_HIP(launch_gather_i32(crow, ws.sel_rows, rows, cache_row_out, s));
     }
     if (rows == 0) return CB_OK;
     sel_rows = ws.sel_rows;
     {
       // only the kept tokens' KV is updated (Sec. 6)
       ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)rows * 4 * kv_dim * es);
-      CB_HIP(launch_scatter_kv(dt, ws.kvnew, sel_rows, pos_out, rows, kc, vc, kv_dim, s));
+      CB_HIP(launch_scatter_kv(dt, ws.kvnew, sel_rows, cache_row_out ? cache_row_out : pos_out, rows, kc, vc,
+                               kv_dim, s));
     }
     if (!q_all) {
       g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
@@ -231,11 +259,13 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     {
       ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)n * 8);
       CB_HIP(hipMemcpyAsync(pos_out, row_pos, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
+      if (cache_row_out)
+        CB_HIP(hipMemcpyAsync(cache_row_out, crow, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
     }
     g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = 3;
     g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
-    g.seg[1] = {w->wk, kv_dim, kc, kv_dim, row_pos, 1};
-    g.seg[2] = {w->wv, kv_dim, vc, kv_dim, row_pos, 0};
+    g.seg[1] = {w->wk, kv_dim, kc, kv_dim, crow, 1};
+    g.seg[2] = {w->wv, kv_dim, vc, kv_dim, crow, 0};
     g.row_pos = row_pos;
     {
       ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * (q_dim + 2 * kv_dim),
@@ -248,9 +278,19 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     }
   }
   {
+    // attention is per request: its rows against its own cache slab
     ProfScope ps(c, s, CB_PROF_ATTN, 0, 0);
-    CB_HIP(launch_attention(dt, ws.qbuf, q_all ? sel_rows : nullptr, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads, m.n_kv_heads,
-                            m.head_dim, n_tokens, ws.partial, ws.partial_floats, s));
+    int out_off = 0;
+    for (int b = 0; b < n_segs; ++b) {
+      const int rows_b = segs[b].k + segs[b].S;
+      const char *q_b = (const char *)ws.qbuf + (q_all ? 0 : (size_t)out_off * q_dim * es);
+      CB_HIP(launch_attention(dt, q_b, q_all ? sel_rows + out_off : nullptr, pos_out + out_off, rows_b,
+                              (char *)kc + (size_t)b * cache_stride * kv_dim * es,
+                              (char *)vc + (size_t)b * cache_stride * kv_dim * es,
+                              (char *)ws.obuf + (size_t)out_off * q_dim * es, m.n_q_heads, m.n_kv_heads,
+                              m.head_dim, segs[b].T, ws.partial, ws.partial_floats, s));
+      out_off += rows_b;
+    }
   }
   // h = H + o Wo^T
   GemmArgs f = {};
@@ -430,8 +470,9 @@ int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const flo
   if (n_rows == 0) return CB_OK;
   LayerWs ws = carve_layer(c, (char *)workspace, n_rows);
   if (ws.bytes > workspace_bytes) return CB_EWORKSPACE;
-  return fuse_layer_impl(c, w, h_in, row_pos, n_rows, n_suffix, k_cache, v_cache, n_tokens_total, k_keep, forced_sel,
-                         h_out, pos_out, dev_out, ws, (hipStream_t)stream);
+  const Seg seg = {n_rows, n_suffix, k_keep, n_tokens_total};
+  return fuse_layer_impl(c, w, h_in, row_pos, nullptr, &seg, 1, 0, k_cache, v_cache, forced_sel, h_out, pos_out,
+                         nullptr, dev_out, ws, (hipStream_t)stream);
 }
 
 namespace {
@@ -500,7 +541,7 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
   {
     ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)T * d * (4 + esize(c)));
     CB_HIP(launch_to_f32(c->m.dtype, x, h_cur, (size_t)T * d, s));
-    hipLaunchKernelGGL(iota_kernel, dim3((T + 255) / 256), dim3(256), 0, s, p_cur, T);
+    hipLaunchKernelGGL(iota_kernel, dim3((T + 255) / 256), dim3(256), 0, s, p_cur, T, 0);
     CB_HIP(hipGetLastError());
   }
   int st = CB_OK;
@@ -519,8 +560,9 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
     }
     const int32_t *forced = forced_sel ? forced_sel[l] : nullptr;
     float *dev_out = dev_dump ? dev_dump[l] : nullptr;
-    st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, n, n_suffix, k_cache_layers[l], v_cache_layers[l],
-                         T, k, forced, h_nxt, p_nxt, dev_out, ws, s);
+    const Seg seg = {n, n_suffix, k, T};
+    st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, nullptr, &seg, 1, 0, k_cache_layers[l], v_cache_layers[l],
+                         forced, h_nxt, p_nxt, nullptr, dev_out, ws, s);
     if (st != CB_OK) return st;
     if (sel_dump && sel_dump[l] && k > 0)
       CB_HIP(hipMemcpyAsync(sel_dump[l], p_nxt, (size_t)k * 4, hipMemcpyDeviceToDevice, s));
@@ -558,6 +600,117 @@ int cb_fuse_prefill_pipelined(cb_ctx *c, const cb_layer_weights *layers, const v
   return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, k_host_layers, v_host_layers,
                       k_cache_layers, v_cache_layers, keep_counts, nullptr, final_hidden, nullptr, nullptr,
                       workspace, workspace_bytes, stream, copy_stream);
+}
+
+size_t cb_batched_workspace_bytes(const cb_ctx *c, int32_t total_tokens) {
+  if (!c || total_tokens < 1) return 0;
+  const size_t h = align_up((size_t)total_tokens * c->m.d_model * 4, 256);
+  const size_t p = align_up((size_t)total_tokens * 4, 256);
+  return 2 * h + 4 * p + carve_layer(c, nullptr, total_tokens).bytes;
+}
+
+int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n_requests, const void *x,
+                            const int32_t *chunk_lens, const int32_t *n_chunks, const int32_t *n_suffix,
+                            void *const *k_cache_layers, void *const *v_cache_layers, int32_t cache_stride,
+                            const int32_t *keep_counts, float *final_hidden, int32_t *const *sel_dump,
+                            float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !layers || !x || !chunk_lens || !n_chunks || !n_suffix || !k_cache_layers || !v_cache_layers ||
+      !keep_counts || !workspace)
+    return CB_ENULL;
+  if (n_requests < 1 || n_requests > 1024 || cache_stride < 1) return CB_EINVAL;
+  const int B = n_requests, L = c->m.n_layers, d = c->m.d_model;
+  const size_t es = esize(c), kv_row = (size_t)c->m.n_kv_heads * c->m.head_dim * es;
+  std::vector<std::vector<int32_t>> off(B);
+  std::vector<int> C(B), T(B);
+  long total = 0, total_suffix = 0;
+  int ci = 0;
+  for (int b = 0; b < B; ++b) {
+    if (n_chunks[b] < 1 || n_suffix[b] < 0) return CB_EINVAL;
+    off[b].assign(n_chunks[b] + 1, 0);
+    for (int i = 0; i < n_chunks[b]; ++i, ++ci) {
+      if (chunk_lens[ci] < 1 || (long)off[b][i] + chunk_lens[ci] > c->max_tokens) return CB_EINVAL;
+      off[b][i + 1] = off[b][i] + chunk_lens[ci];
+    }
+    C[b] = off[b][n_chunks[b]];
+    T[b] = C[b] + n_suffix[b];
+    if (T[b] > c->max_tokens || T[b] > cache_stride) return CB_EINVAL;
+    if (keep_counts[(size_t)b * L] != C[b]) return CB_EINVAL;
+    for (int l = 1; l < L; ++l)
+      if (keep_counts[(size_t)b * L + l] < 0 || keep_counts[(size_t)b * L + l] > keep_counts[(size_t)b * L + l - 1])
+        return CB_EINVAL;
+    total += T[b];
+    total_suffix += n_suffix[b];
+  }
+  if (total > (1 << 24) || (long)B * cache_stride > (1L << 30)) return CB_EINVAL;
+  if (total_suffix > 0 && !final_hidden) return CB_ENULL;
+  for (int l = 0; l < L; ++l) {
+    if (!k_cache_layers[l] || !v_cache_layers[l]) return CB_ENULL;
+    const cb_layer_weights *w = &layers[l];
+    if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up ||
+        !w->w_down)
+      return CB_ENULL;
+  }
+  const int N = (int)total;
+  if (cb_batched_workspace_bytes(c, N) > workspace_bytes) return CB_EWORKSPACE;
+
+  hipStream_t s = (hipStream_t)stream;
+  char *base = (char *)workspace;
+  const size_t hb = align_up((size_t)N * d * 4, 256), pb = align_up((size_t)N * 4, 256);
+  float *h_cur = (float *)base, *h_nxt = (float *)(base + hb);
+  int32_t *p_cur = (int32_t *)(base + 2 * hb), *p_nxt = (int32_t *)(base + 2 * hb + pb);
+  int32_t *r_cur = (int32_t *)(base + 2 * hb + 2 * pb), *r_nxt = (int32_t *)(base + 2 * hb + 3 * pb);
+  LayerWs ws = carve_layer(c, base + 2 * hb + 4 * pb, N);
+
+  {
+    ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)N * d * (4 + es));
+    CB_HIP(launch_to_f32(c->m.dtype, x, h_cur, (size_t)N * d, s));
+    int o = 0;
+    for (int b = 0; b < B; ++b) {
+      hipLaunchKernelGGL(iota_kernel, dim3((T[b] + 255) / 256), dim3(256), 0, s, p_cur + o, T[b], 0);
+      hipLaunchKernelGGL(iota_kernel, dim3((T[b] + 255) / 256), dim3(256), 0, s, r_cur + o, T[b], b * cache_stride);
+      o += T[b];
+    }
+    CB_HIP(hipGetLastError());
+  }
+  std::vector<void *> kptr(L);
+  for (int b = 0; b < B; ++b) {
+    for (int l = 0; l < L; ++l) kptr[l] = (char *)k_cache_layers[l] + (size_t)b * cache_stride * kv_row;
+    int st = cb_realign_rope(c, kptr.data(), 0, L, off[b].data(), n_chunks[b], stream);
+    if (st != CB_OK) return st;
+  }
+
+  std::vector<Seg> segs(B);
+  for (int b = 0; b < B; ++b) segs[b] = {T[b], n_suffix[b], 0, T[b]};
+  for (int l = 0; l < L; ++l) {
+    for (int b = 0; b < B; ++b) segs[b].k = keep_counts[(size_t)b * L + l];
+    int st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, r_cur, segs.data(), B, (size_t)cache_stride,
+                             k_cache_layers[l], v_cache_layers[l], nullptr, h_nxt, p_nxt, r_nxt,
+                             dev_dump ? dev_dump[l] : nullptr, ws, s);
+    if (st != CB_OK) return st;
+    int o = 0;
+    for (int b = 0; b < B; ++b) {
+      int32_t *dst = sel_dump ? sel_dump[(size_t)b * L + l] : nullptr;
+      if (dst && segs[b].k > 0)
+        CB_HIP(hipMemcpyAsync(dst, p_nxt + o, (size_t)segs[b].k * 4, hipMemcpyDeviceToDevice, s));
+      o += segs[b].k + segs[b].S;
+      segs[b].n = segs[b].k + segs[b].S;
+    }
+    std::swap(h_cur, h_nxt);
+    std::swap(p_cur, p_nxt);
+    std::swap(r_cur, r_nxt);
+  }
+  {
+    ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)total_suffix * d * 8);
+    int o = 0, fo = 0;
+    for (int b = 0; b < B; ++b) {
+      if (segs[b].S > 0)
+        CB_HIP(launch_copy_rows_f32(h_cur + (size_t)(o + segs[b].n - segs[b].S) * d, final_hidden + (size_t)fo * d,
+                                    (size_t)segs[b].S * d, s));
+      o += segs[b].n;
+      fo += segs[b].S;
+    }
+  }
+  return CB_OK;
 }
 
 int cb_first_token(cb_ctx *c, const float *final_hidden, int32_t n_suffix, const void *final_norm,

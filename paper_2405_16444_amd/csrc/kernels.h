@@ -28,11 +28,13 @@ hipError_t launch_scatter_kv(int dtype, const void *kvnew, const int32_t *sel_ro
 hipError_t launch_copy_rows_f32(const float *in, float *out, size_t n, hipStream_t s);
 
 // ---- select.hip ------------------------------------------------------------
-// Keep the k largest of dev[0..n_cand) (ties -> lower index); sel_rows[0..k) = kept row
-// indices ascending, then the n_suffix rows n_cand..n_cand+n_suffix-1; pos_out[i] =
-// row_pos[sel_rows[i]].  One workgroup.
+// Keep the k largest of dev[0..n_cand) (ties -> lower index); sel_rows[0..k) = row_base + kept
+// row indices ascending, then the n_suffix rows row_base + n_cand ..; pos_out[i] = row_pos of
+// that row (row_pos indexed without row_base).  One workgroup.
 hipError_t launch_topk(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
-                       int32_t *sel_rows, int32_t *pos_out, hipStream_t s);
+                       int32_t *sel_rows, int32_t *pos_out, int row_base, hipStream_t s);
+// out[i] = src[idx[i]], i < n.
+hipError_t launch_gather_i32(const int32_t *src, const int32_t *idx, int n, int32_t *out, hipStream_t s);
 // Same outputs from a given ascending list of positions (lower-bound search in row_pos).
 hipError_t launch_forced_map(const int32_t *forced, int k, const int32_t *row_pos, int n_cand,
                              int n_suffix, int32_t *sel_rows, int32_t *pos_out, hipStream_t s);

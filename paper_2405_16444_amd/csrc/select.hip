@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float *__restri
                                                            int n_suffix,
                                                            const int32_t *__restrict__ row_pos,
                                                            int32_t *__restrict__ sel_rows,
-                                                           int32_t *__restrict__ pos_out) {
+                                                           int32_t *__restrict__ pos_out, int row_base) {
   __shared__ unsigned hist[256];
   __shared__ unsigned s_prefix, s_need;
   __shared__ int wave_tot[kSelWaves];
@@ -106,23 +106,23 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float *__restri
     const bool take = gt || (eq && (unsigned)eq_rank < need);
     int o = out_base + block_excl_count(take, wave_tot, &tot_take);
     if (take) {
-      sel_rows[o] = i;
+      sel_rows[o] = row_base + i;
       pos_out[o] = row_pos[i];
     }
     eq_seen += tot_eq;
     out_base += tot_take;
   }
   for (int i = tid; i < n_suffix; i += kSelThreads) {
-    sel_rows[k + i] = n + i;
+    sel_rows[k + i] = row_base + n + i;
     pos_out[k + i] = row_pos[n + i];
   }
 }
 
 hipError_t launch_topk(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
-                       int32_t *sel_rows, int32_t *pos_out, hipStream_t s) {
+                       int32_t *sel_rows, int32_t *pos_out, int row_base, hipStream_t s) {
   if (k + n_suffix == 0) return hipSuccess;
   hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(kSelThreads), 0, s, dev, n_cand, k, n_suffix, row_pos,
-                     sel_rows, pos_out);
+                     sel_rows, pos_out, row_base);
   return hipGetLastError();
 }
 
@@ -153,6 +153,18 @@ hipError_t launch_forced_map(const int32_t *forced, int k, const int32_t *row_po
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(forced_map_kernel, dim3((n + 255) / 256), dim3(256), 0, s, forced, k, row_pos,
                      n_cand, n_suffix, sel_rows, pos_out);
+  return hipGetLastError();
+}
+
+__global__ void gather_i32_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ idx, int n,
+                                  int32_t *__restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = src[idx[i]];
+}
+
+hipError_t launch_gather_i32(const int32_t *src, const int32_t *idx, int n, int32_t *out, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, src, idx, n, out);
   return hipGetLastError();
 }
 

@@ -1,0 +1,146 @@
+"""Several requests stacked in one call: every request is held against the oracle on its own
+(the oracle has no notion of a batch: a batch is B independent requests), with the same parity
+protocol as a single request -- kept sets bit-exact for the GPU's deviation vector, caches and
+hidden states within tolerance with the oracle forced to the GPU's selections."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cacheblend_oracle as O
+from workloads import synth
+from workloads.configs import Workload
+
+from gpu_util import TOL, announce, dev_layers, max_abs_rel, np_layers, oracle_caches, scaled_weights, to_np
+from test_gpu_parity import MODELS
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2405_16444_amd as pkg
+    return pkg
+
+
+def make_requests(model, specs, seed):
+    """specs: (chunk_lens, n_suffix, keep fractions per layer) per request; one model for all."""
+    layers = scaled_weights(model, seed, 0.07)
+    npl = np_layers(layers)
+    reqs = []
+    for i, (lens, S, fr) in enumerate(specs):
+        w = Workload(f"req{i}", model, tuple(lens), S, 0.15, 0.30, seed, seed + 10 + i)
+        x = synth.hidden_inputs(w)
+        xn = synth.to_f64(x)
+        kpre, vpre = oracle_caches(w, npl, xn)
+        keep = [w.n_ctx] + [int(np.ceil(f * w.n_ctx)) for f in fr[1:]]
+        for l in range(1, len(keep)):
+            keep[l] = min(keep[l], keep[l - 1])
+        reqs.append(dict(w=w, x=x, xn=xn, kpre=kpre, vpre=vpre, keep=keep))
+    return layers, npl, reqs
+
+
+def run_batched(P, model, layers, reqs, stride):
+    B, L = len(reqs), model.n_layers
+    dt = synth.storage_dtype(model)
+    ctx = P.cb_create(model, max(r["w"].n_tokens for r in reqs))
+    x = torch.cat([r["x"] for r in reqs]).cuda().contiguous()
+    kc, vc = [], []
+    for l in range(L):
+        k = torch.full((B * stride, model.n_kv_heads, model.head_dim), 3.0, dtype=dt, device="cuda")
+        v = torch.full_like(k, -5.0)
+        for b, r in enumerate(reqs):
+            C = r["w"].n_ctx
+            k[b * stride:b * stride + C] = torch.from_numpy(r["kpre"][l]).to(dt).cuda()
+            v[b * stride:b * stride + C] = torch.from_numpy(r["vpre"][l]).to(dt).cuda()
+        kc.append(k)
+        vc.append(v)
+    out = P.cb_fuse_prefill_batched(ctx, dev_layers(layers), x, [r["w"].chunk_lens for r in reqs],
+                                    [r["w"].n_suffix for r in reqs], kc, vc, stride, [r["keep"] for r in reqs],
+                                    want_sel=True, want_dev=True)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    return out, kc, vc
+
+
+def check_request(b, r, npl, model, out, kc, vc, stride, rows_in, tol):
+    """rows_in[l][b] = (offset of the request's rows in layer l's stacked input, its candidate count)."""
+    w, keep = r["w"], r["keep"]
+    rnd = O.storage_round(model.dtype)
+    sel = [out.sel[b][l].cpu().numpy().astype(np.int64) for l in range(model.n_layers)]
+    cand = np.arange(w.n_ctx)
+    for l, k in enumerate(keep):
+        off, n_cand = rows_in[l][b]
+        if k < len(cand):
+            d = out.dev[l].cpu().numpy()[off:off + n_cand]
+            assert np.array_equal(sel[l], cand[O.top_k_indices(d, k)]), f"request {b} layer {l}"
+        else:
+            assert np.array_equal(sel[l], cand)
+        cand = sel[l]
+    ref = O.fuse_prefill(r["xn"], npl, model, w.chunk_lens, w.n_suffix, r["kpre"], r["vpre"], keep,
+                         forced_sel=sel, kv_round=rnd)
+    for l in range(model.n_layers):
+        kg = kc[l][b * stride:b * stride + w.n_tokens].cpu()
+        vg = vc[l][b * stride:b * stride + w.n_tokens].cpu()
+        assert max_abs_rel(to_np(kg), ref.K[l]) < tol and max_abs_rel(to_np(vg), ref.V[l]) < tol, f"req {b} layer {l}"
+        if keep[l] < (w.n_ctx if l == 0 else keep[l - 1]):
+            off, n_cand = rows_in[l][b]
+            got = out.dev[l].cpu().numpy()[off:off + n_cand]
+            if ref.dev[l].max() < 1e-9:        # a single chunk is a prefix: its deviation is rounding noise
+                assert got.max() < (1e-6 if model.dtype == "f32" else 0.05)
+            else:
+                assert max_abs_rel(got, ref.dev[l]) < tol
+    return ref
+
+
+@pytest.mark.parametrize("name,specs", [
+    ("f32", [((60, 45, 70), 7, (1.0, 0.4, 0.2)), ((33, 90), 12, (1.0, 0.5, 0.5)), ((128,), 1, (1.0, 0.3, 0.1))]),
+    ("bf16", [((150, 97, 200), 21, (1.0, 0.35, 0.15)), ((64, 64, 64, 64), 32, (1.0, 0.9, 0.85))]),
+    ("bf16_g7", [((80, 120), 10, (1.0, 1.0, 1.0)), ((90, 70, 50), 5, (1.0, 1.0, 1.0))]),     # no check at all
+])
+def test_batched_requests_each_match_the_oracle(P, name, specs):
+    model = replace(MODELS[name], n_layers=3)
+    announce("batched", name, [s[0] for s in specs])
+    layers, npl, reqs = make_requests(model, specs, seed=77)
+    stride = max(r["w"].n_tokens for r in reqs) + 5
+    out, kc, vc = run_batched(P, model, layers, reqs, stride)
+    tol = TOL[model.dtype]
+    # where each request's rows sit in every layer's stacked input
+    rows_in, n_b = [], [r["w"].n_tokens for r in reqs]
+    for l in range(model.n_layers):
+        offs, o = [], 0
+        for b, r in enumerate(reqs):
+            offs.append((o, n_b[b] - r["w"].n_suffix))
+            o += n_b[b]
+        rows_in.append(offs)
+        n_b = [r["keep"][l] + r["w"].n_suffix for r in reqs]
+    fo = 0
+    for b, r in enumerate(reqs):
+        ref = check_request(b, r, npl, model, out, kc, vc, stride, rows_in, tol)
+        S = r["w"].n_suffix
+        assert max_abs_rel(to_np(out.final_hidden[fo:fo + S].cpu()), ref.final_hidden) < tol
+        fo += S
+    # rows between the slabs are never written
+    for l in range(model.n_layers):
+        for b, r in enumerate(reqs):
+            gap = kc[l][b * stride + r["w"].n_tokens:(b + 1) * stride]
+            assert bool((gap == 3.0).all())
+
+
+def test_batch_of_one_equals_the_single_request_entry_bitwise(P):
+    model = replace(MODELS["bf16"], n_layers=3)
+    announce("batched, one request")
+    layers, npl, reqs = make_requests(model, [((150, 97, 200), 21, (1.0, 0.35, 0.15))], seed=78)
+    r = reqs[0]
+    out, kc, vc = run_batched(P, model, layers, reqs, r["w"].n_tokens)
+    from gpu_util import cache_tensors
+    ctx = P.cb_create(model, r["w"].n_tokens)
+    kg, vg = cache_tensors(r["w"], r["kpre"], r["vpre"])
+    single = P.cb_fuse_prefill(ctx, dev_layers(layers), r["x"].cuda(), r["w"].chunk_lens, r["w"].n_suffix, kg, vg,
+                               r["keep"])
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    assert torch.equal(single.final_hidden, out.final_hidden)
+    for l in range(model.n_layers):
+        assert torch.equal(kg[l], kc[l]) and torch.equal(vg[l], vc[l])
