@@ -407,7 +407,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     // (tile tn, step ksn, into the other buffer) and -- when `refill` -- the global loads of the
     // next stages slotted in between them.  A wavefront issues in order and has its SIMD to
     // itself, so anything not placed between two MFMAs would add to the MFMA time.
-    auto step = [&](int buf, bool next_reads, int tn, int ksn, bool refill, int tl) {
+    auto step = [&](int buf, bool next_reads, int tn, int ksn, int q0, int q1, int tl) {
       const unsigned base_w = lds0 + W_RING + (tn % SW) * W_STAGE + b_off + rd[ksn];
       const unsigned base_a = lds0 + (tn % DMA_SA) * A_STAGE + a_off + rd[ksn];
 #pragma unroll
@@ -415,10 +415,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
         if (j < NM)
           acc[j / NB][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / NB], fb[buf][j % NB],
                                                                        acc[j / NB][j % NB], 0, 0, 0);
-        if (refill) {
+        // global loads q0 .. q1-1 of tile tl, spread evenly over the slots of this k-step
 #pragma unroll
-          for (int q = j * NL / NSLOT; q < (j + 1) * NL / NSLOT; ++q) issue_one(tl, q);
-        }
+        for (int q = q0 + j * (q1 - q0) / NSLOT; q < q0 + (j + 1) * (q1 - q0) / NSLOT; ++q) issue_one(tl, q);
         if (next_reads && j < NF) read_one(base_w, base_a, buf ^ 1, j);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -428,9 +427,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
       }
     };
 
-    // Issue order: W(0..SW-2), A(0), then at the barrier of tile t: A(t+2) and W(t+SW) interleaved
-    // (activation loads first).  When tile t+1 is needed, the only loads that may be younger than
-    // the last load of A(t+1) are the LW loads of W(t+SW-1).
+    // Issue order: W(0..SW-2), A(0), A(1), W(SW-1) up front; from then on the loads of a tile are
+    // spread over four k-steps so that the memory pipeline never sees a burst: after the barrier
+    // of tile t (its stages are free) the first half of A(t+2); during the first three k-steps of
+    // tile t+1 the second half of A(t+2), then W(t+SW) in two halves.  When tile t+1 is needed,
+    // the only loads that may be younger than the last load of A(t+1) are the LW loads of
+    // W(t+SW-1).
+    constexpr int QA = LA / 2, QW = LA + LW / 2;
 #pragma unroll
     for (int s = 0; s < SW - 1; ++s) issue_w(s);
 #pragma unroll
@@ -443,20 +446,29 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     for (int q = 0; q < NF; ++q) read_one(lds0 + W_RING + b_off + rd[0], lds0 + a_off + rd[0], 0, q);
     lds_wait<0>();
     pin(0);
-    for (int t = 0; t + 1 < nk; ++t) {
-      step(0, true, t, 1, false, 0);
-      step(1, true, t, 2, false, 0);
-      step(0, true, t, 3, false, 0);
+    if (nk > 1) {
+      // tile 0: tile 1 is already on its way
+      step(0, true, 0, 1, 0, 0, 0);
+      step(1, true, 0, 2, 0, 0, 0);
+      step(0, true, 0, 3, 0, 0, 0);
+      vm_wait<LW>();
+      wg_barrier();
+      step(1, true, 1, 0, 0, QA, 2);
+    }
+    for (int t = 1; t + 1 < nk; ++t) {
+      step(0, true, t, 1, QA, LA, t + 1);
+      step(1, true, t, 2, LA, QW, t + 1);
+      step(0, true, t, 3, QW, NL, t + 1);
       // last k-step: fragments are in registers, so once tile t+1 has landed everywhere the
       // stages of tile t can be refilled while these MFMAs run
       vm_wait<LW>();
       wg_barrier();
-      step(1, true, t + 1, 0, true, t + 2);
+      step(1, true, t + 1, 0, 0, QA, t + 2);
     }
-    step(0, true, nk - 1, 1, false, 0);
-    step(1, true, nk - 1, 2, false, 0);
-    step(0, true, nk - 1, 3, false, 0);
-    step(1, false, 0, 0, false, 0);
+    step(0, true, nk - 1, 1, 0, 0, 0);
+    step(1, true, nk - 1, 2, 0, 0, 0);
+    step(0, true, nk - 1, 3, 0, 0, 0);
+    step(1, false, 0, 0, 0, 0, 0);
   }
   if (EPI == EPI_SWIGLU && tail_z >= 0) {
     // raw partial sums of a shared tile, in register order (each store is 256 contiguous bytes)
