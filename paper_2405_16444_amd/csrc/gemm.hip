@@ -214,26 +214,26 @@ __device__ __forceinline__ void xcd_tile(int j, int xcd, int tiles_m, int nblk, 
   *mt = g * kGroupM + r % gm;
 }
 
-// silu(gate) * up from one wavefront's accumulators of a (32*I) x (64*NB) tile: blocks
-// 0..NB/2-1 of a lane hold gate columns, blocks NB/2..NB-1 the same columns of the up matrix;
-// lane l holds column (l % 32) of each block and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row block.
-template <int I, int NB>
-__device__ __forceinline__ void swiglu_from_registers(const f32x16 (&acc)[I / 2][NB], const GemmParams &p,
-                                                      int m0, int n0, int wm, int wn, int lane) {
-  constexpr int IH = I / 2, BN = 64 * NB;
+// silu(gate) * up from one wavefront's accumulators (IH x NBW blocks of 32 x 32): blocks
+// 0..NBW/2-1 of a lane hold gate columns, blocks NBW/2..NBW-1 the same columns of the up matrix;
+// lane l holds column (l % 32) of each block and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row
+// block.  row0 / col0: first output row / column of the wavefront.
+template <int IH, int NBW>
+__device__ __forceinline__ void swiglu_from_registers(const f32x16 (&acc)[IH][NBW], const GemmParams &p,
+                                                      int row0, int col0, int lane) {
   const int h = lane >> 5, ln = lane & 31;
 #pragma unroll
   for (int i = 0; i < IH; ++i) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int gr = m0 + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+      const int gr = row0 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
       if (gr >= p.M) continue;
       bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
 #pragma unroll
-      for (int jb = 0; jb < NB / 2; ++jb) {
-        const int gc = n0 + wn * (BN / 4) + jb * 32 + ln;
+      for (int jb = 0; jb < NBW / 2; ++jb) {
+        const int gc = col0 + jb * 32 + ln;
         if (gc >= p.N) continue;
-        const float gt = acc[i][jb][r], up = acc[i][jb + NB / 2][r];
+        const float gt = acc[i][jb][r], up = acc[i][jb + NBW / 2][r];
         // silu(g) * u = g * u / (1 + 2^(-g log2 e))
         const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt);
         orow[gc] = (bf16)(gt * up * __builtin_amdgcn_rcpf(den));
@@ -246,10 +246,10 @@ __device__ __forceinline__ void swiglu_from_registers(const f32x16 (&acc)[I / 2]
 // sums lie in register order: [slot][split][wavefront][row block i][column block jb][r][lane].
 // One wavefront here owns one (wavefront, i, gate block jb) unit of a tile: it adds the gate and
 // the up block over the splits in ascending K order and applies the epilogue.
-template <int I, int NB>
+template <int I, int NB, int NWV>
 __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tiles_m, int tiles_n) {
-  constexpr int IH = I / 2, BM = 32 * I, BN = 64 * NB, HB = NB / 2;
-  constexpr int UNITS = 4 * IH * HB;                      // per tile
+  constexpr int IH = I / 2, BM = 32 * I, BN = 64 * NB, WN = NWV / 2, NBW = 2 * NB / WN, HB = NBW / 2;
+  constexpr int UNITS = NWV * IH * HB;                    // per tile
   const int lane = threadIdx.x & 63;
   const int slot = blockIdx.x / (UNITS / 4);
   const int u = (blockIdx.x % (UNITS / 4)) * 4 + (threadIdx.x >> 6);
@@ -258,8 +258,8 @@ __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tile
   int nt, mt;
   xcd_tile(j, xcd, tiles_m, (tiles_n + 7) >> 3, &nt, &mt);
   if (nt >= tiles_n) return;
-  const float *pg = p.partial + (size_t)slot * p.tail_splits * (BM * BN) + (size_t)wave * (IH * NB * 16 * 64) +
-                    (size_t)(i * NB + jb) * (16 * 64) + lane;
+  const float *pg = p.partial + (size_t)slot * p.tail_splits * (BM * BN) + (size_t)wave * (IH * NBW * 16 * 64) +
+                    (size_t)(i * NBW + jb) * (16 * 64) + lane;
   float gate[16], up[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) gate[r] = up[r] = 0.f;
@@ -270,8 +270,8 @@ __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tile
       up[r] += pg[(HB * 16 + r) * 64];
     }
   }
-  const int wm = wave >> 1, wn = wave & 1, h = lane >> 5, ln = lane & 31;
-  const int gc = nt * (BN / 2) + wn * (BN / 4) + jb * 32 + ln;
+  const int wm = wave / WN, wn = wave % WN, h = lane >> 5, ln = lane & 31;
+  const int gc = nt * (BN / 2) + wn * (BN / WN / 2) + jb * 32 + ln;
   if (gc >= p.N) return;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -282,18 +282,20 @@ __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tile
   }
 }
 
-template <int I, int NB, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
+template <int I, int NB, int EPI, int NWV>
+__global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN), DMA_CP = BN + 4;
   constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128, W_RING = DMA_SA * A_STAGE;
-  constexpr int LA = BM / 32, LW = BN / 32;              // 16-byte loads per lane per tile (8 rows x 4 waves each)
+  constexpr int WN = NWV / 2;                            // wavefronts as 2 x WN
+  constexpr int NBW = 2 * NB / WN;                       // 32-column blocks per wavefront
+  constexpr int LA = BM / (8 * NWV), LW = BN / (8 * NWV); // 16-byte loads per lane per tile (8 rows per wavefront each)
   static_assert(SW >= 3, "the vmcnt bookkeeping below assumes at least 3 weight stages");
   constexpr int IH = I / 2;                              // row blocks per wavefront
-  constexpr int NF = IH + NB;                            // operand reads per k-step per wavefront
+  constexpr int NF = IH + NBW;                           // operand reads per k-step per wavefront
   constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;               // 2 x 2 wavefronts, (BM/2) x 128 each
+  const int wm = wave / WN, wn = wave % WN;              // 2 x WN wavefronts, (BM/2) x (BN/WN) each
 
   // XCD-aware tile order
   int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, tail_z = -1;
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   const bf16 *src_a[LA], *src_w[LW];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
-    const int r = (wave + 4 * i) * 8 + (lane >> 3);           // row of the activation tile
+    const int r = (wave + NWV * i) * 8 + (lane >> 3);         // row of the activation tile
     const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
     int ar = min(m0 + r, p.M - 1);
     if (p.a_rows) ar = p.a_rows[ar];
@@ -326,13 +328,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   }
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
-    const int r = (wave + 4 * i) * 8 + (lane >> 3);           // row of the weight tile
+    const int r = (wave + NWV * i) * 8 + (lane >> 3);         // row of the weight tile
     const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
     const bf16 *wrow;
     if (EPI == EPI_SWIGLU) {
       // each wavefront's half of the tile columns holds its gate columns followed by the SAME
       // up columns, so that a lane ends up with gate and up of one output element
-      constexpr int WC = BN / 2, HC = BN / 4;          // columns per wavefront / per operand
+      constexpr int WC = BN / WN, HC = WC / 2;         // columns per wavefront / per operand
       const int which = (r % WC) / HC, oc = min(n0 + (r / WC) * HC + (r % HC), p.N - 1);
       wrow = reinterpret_cast<const bf16 *>(p.w[which]) + (size_t)oc * p.K;
     } else {
@@ -345,25 +347,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   auto issue_one = [&](int t, int idx) {
     if (idx < LA) {
       const int k0 = min(t, nk - 1) * DMA_BK;
-      CB_GLDS16(src_a[idx] + k0, smem + (t % DMA_SA) * A_STAGE + (wave + 4 * idx) * 1024);
+      CB_GLDS16(src_a[idx] + k0, smem + (t % DMA_SA) * A_STAGE + (wave + NWV * idx) * 1024);
     } else {
       const int tw = t + SW - DMA_SA;                 // the weight ring runs SW - 2 tiles further ahead
       const int k0 = min(tw, nk - 1) * DMA_BK;
-      CB_GLDS16(src_w[idx - LA] + k0, smem + W_RING + (tw % SW) * W_STAGE + (wave + 4 * (idx - LA)) * 1024);
+      CB_GLDS16(src_w[idx - LA] + k0, smem + W_RING + (tw % SW) * W_STAGE + (wave + NWV * (idx - LA)) * 1024);
     }
   };
   auto issue_w = [&](int t) {
     const int k0 = min(t, nk - 1) * DMA_BK;
 #pragma unroll
     for (int i = 0; i < LW; ++i)
-      CB_GLDS16(src_w[i] + k0, smem + W_RING + (t % SW) * W_STAGE + (wave + 4 * i) * 1024);
+      CB_GLDS16(src_w[i] + k0, smem + W_RING + (t % SW) * W_STAGE + (wave + NWV * i) * 1024);
   };
 
-  f32x16 acc[IH][NB];
+  f32x16 acc[IH][NBW];
 #pragma unroll
   for (int i = 0; i < IH; ++i)
 #pragma unroll
-    for (int jb = 0; jb < NB; ++jb)
+    for (int jb = 0; jb < NBW; ++jb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][jb][r] = 0.f;
 
@@ -372,23 +374,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     int rd[4];                                                    // k-step ks reads chunk 2*ks + h
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) rd[ks] = (lane & 31) * 128 + (((2 * ks + h) ^ sw) << 4);
-    const int a_off = (wm * IH * 32) * 128, b_off = (wn * (BN / 2)) * 128;
-    bf16x8 fa[2][IH], fb[2][NB];
-    constexpr int NM = IH * NB;                        // MFMAs per k-step per wavefront
+    const int a_off = (wm * IH * 32) * 128, b_off = (wn * (BN / WN)) * 128;
+    bf16x8 fa[2][IH], fb[2][NBW];
+    constexpr int NM = IH * NBW;                       // MFMAs per k-step per wavefront
     constexpr int NL = LA + LW;                        // loads per tile per lane
     constexpr int NSLOT = NM > NF ? NM : NF;
     // operand read number idx (0..NF-1) into fragment buffer buf; base_w / base_a are the LDS
     // byte addresses of this lane's first weight / activation fragment of the k-step
     auto read_one = [&](unsigned base_w, unsigned base_a, int buf, int idx) {
-      if (idx < NB) {
+      if (idx < NBW) {
         switch (idx) {
           case 0: lds_read16<0>(fb[buf][0], base_w); break;
-          case 1: lds_read16<4096>(fb[buf][1], base_w); break;
-          case 2: if (NB > 2) lds_read16<8192>(fb[buf][NB > 2 ? 2 : 0], base_w); break;
-          default: if (NB > 3) lds_read16<12288>(fb[buf][NB > 3 ? 3 : 0], base_w); break;
+          case 1: if (NBW > 1) lds_read16<4096>(fb[buf][NBW > 1 ? 1 : 0], base_w); break;
+          case 2: if (NBW > 2) lds_read16<8192>(fb[buf][NBW > 2 ? 2 : 0], base_w); break;
+          default: if (NBW > 3) lds_read16<12288>(fb[buf][NBW > 3 ? 3 : 0], base_w); break;
         }
       } else {
-        switch (idx - NB) {
+        switch (idx - NBW) {
           case 0: lds_read16<0>(fa[buf][0], base_a); break;
           case 1: if (IH > 1) lds_read16<4096>(fa[buf][IH > 1 ? 1 : 0], base_a); break;
           case 2: if (IH > 2) lds_read16<8192>(fa[buf][IH > 2 ? 2 : 0], base_a); break;
@@ -399,7 +401,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
     const unsigned lds0 = (unsigned)(size_t)smem;
     auto pin = [&](int buf) {
 #pragma unroll
-      for (int jb = 0; jb < NB; ++jb) lds_pin(fb[buf][jb]);
+      for (int jb = 0; jb < NBW; ++jb) lds_pin(fb[buf][jb]);
 #pragma unroll
       for (int i = 0; i < IH; ++i) lds_pin(fa[buf][i]);
     };
@@ -413,8 +415,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
 #pragma unroll
       for (int j = 0; j < NSLOT; ++j) {
         if (j < NM)
-          acc[j / NB][j % NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / NB], fb[buf][j % NB],
-                                                                       acc[j / NB][j % NB], 0, 0, 0);
+          acc[j / NBW][j % NBW] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / NBW], fb[buf][j % NBW],
+                                                                         acc[j / NBW][j % NBW], 0, 0, 0);
         // global loads q0 .. q1-1 of tile tl, spread evenly over the slots of this k-step
 #pragma unroll
         for (int q = q0 + j * (q1 - q0) / NSLOT; q < q0 + (j + 1) * (q1 - q0) / NSLOT; ++q) issue_one(tl, q);
@@ -473,17 +475,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
   if (EPI == EPI_SWIGLU && tail_z >= 0) {
     // raw partial sums of a shared tile, in register order (each store is 256 contiguous bytes)
     const int slot = (j - (p.tail_first >> 3)) * 8 + xcd;
-    float *pb = p.partial + ((size_t)slot * p.tail_splits + tail_z) * (BM * BN) + (size_t)wave * (IH * NB * 16 * 64);
+    float *pb = p.partial + ((size_t)slot * p.tail_splits + tail_z) * (BM * BN) + (size_t)wave * (IH * NBW * 16 * 64);
 #pragma unroll
     for (int i = 0; i < IH; ++i)
 #pragma unroll
-      for (int jb = 0; jb < NB; ++jb)
+      for (int jb = 0; jb < NBW; ++jb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) pb[((i * NB + jb) * 16 + r) * 64 + lane] = acc[i][jb][r];
+        for (int r = 0; r < 16; ++r) pb[((i * NBW + jb) * 16 + r) * 64 + lane] = acc[i][jb][r];
     return;
   }
   if (EPI == EPI_SWIGLU) {
-    swiglu_from_registers<I, NB>(acc, p, m0, n0, wm, wn, lane);
+    swiglu_from_registers<IH, NBW>(acc, p, m0 + wm * IH * 32, n0 + wn * (BN / WN / 2), lane);
     return;
   }
   if (EPI != EPI_SEG) {
@@ -499,8 +501,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
         if (p.splits > 1) {
           float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
 #pragma unroll
-          for (int jb = 0; jb < NB; ++jb) {
-            const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
+          for (int jb = 0; jb < NBW; ++jb) {
+            const int gc = n0 + wn * (BN / WN) + jb * 32 + ln;
             if (gc < p.N) prow[gc] = acc[i][jb][r];
           }
         } else {
@@ -508,8 +510,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
           const float *res = p.resid ? p.resid + (size_t)rr * p.N : nullptr;
           float *orow = p.out_f32 + (size_t)gr * p.N;
 #pragma unroll
-          for (int jb = 0; jb < NB; ++jb) {
-            const int gc = n0 + wn * (BN / 2) + jb * 32 + ln;
+          for (int jb = 0; jb < NBW; ++jb) {
+            const int gc = n0 + wn * (BN / WN) + jb * 32 + ln;
             if (gc < p.N) orow[gc] = acc[i][jb][r] + (res ? res[gc] : 0.f);
           }
         }
@@ -533,11 +535,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_dma_kernel(GemmParams p, int ti
       const int ib = wm * IH + i;                            // this wavefront's row block
       if (ib >= i0 && ib < i0 + 4) {
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
+        for (int jb = 0; jb < NBW; ++jb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int row = (ib - i0) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-            const int col = wn * (BN / 2) + jb * 32 + (lane & 31);
+            const int col = wn * (BN / WN) + jb * 32 + (lane & 31);
             sC[row * DMA_CP + col] = acc[i][jb][r];
           }
       }
@@ -728,7 +730,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p) {
 // ---------------------------------------------------------------------------
 struct GemmPlan {
   int kind;        // 0 float, 1 register-staged bf16, 2 direct-to-LDS bf16
-  int I, NB;       // kind 2: 32-row blocks per tile, 32-column blocks per wavefront (tile = 32I x 64NB)
+  int I, NB;       // kind 2: tile = 32I rows x 64NB columns
+  int nwv;         // kind 2: wavefronts per workgroup (4, or 8 = two per SIMD for the 256-column tiles)
   int bm, out_cols, bk;
   int tiles_m, tiles_n, splits, k_per_split;
   int tail_first, tail_splits, tail_k_per_split;   // EPI_SWIGLU tail sharing (tail_splits <= 1: none)
@@ -804,6 +807,7 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
     pick_dma_plan(M, N, K, &pl);
   }
   if (pl.kind == 2) {
+    pl.nwv = (pl.NB == 4 && pl.I >= 4) ? 8 : 4;
     pl.bm = 32 * pl.I;
     pl.out_cols = (epi == EPI_SWIGLU ? 32 : 64) * pl.NB;
   }
@@ -903,17 +907,17 @@ bool gemm_needs_reduce(const GemmArgs &g) {
   return pl.splits > 1 || pl.tail_splits > 1;
 }
 
-template <int I, int NB, int EPI>
+template <int I, int NB, int EPI, int NWV>
 static void launch_dma(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
   constexpr int smem = dma_smem_bytes(I, 64 * NB);
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<I, NB, EPI>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<I, NB, EPI, NWV>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI>), dim3((unsigned)pl.grid_ids), dim3(256), smem, s, p,
-                     pl.tiles_m, pl.tiles_n);
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI, NWV>), dim3((unsigned)pl.grid_ids), dim3(64 * NWV), smem, s,
+                     p, pl.tiles_m, pl.tiles_n);
 }
 
 template <int EPI>
@@ -929,22 +933,21 @@ static void launch_typed(const GemmPlan &pl, const GemmParams &p, hipStream_t s)
       attr_set = true;
     }
     hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), kSmemBf16, s, p);
-  } else {
-    if (pl.NB == 2) {
-      switch (pl.I) {
-        case 2: launch_dma<2, 2, EPI>(pl, p, s); break;
-        case 4: launch_dma<4, 2, EPI>(pl, p, s); break;
-        case 6: launch_dma<6, 2, EPI>(pl, p, s); break;
-        default: launch_dma<8, 2, EPI>(pl, p, s); break;
-      }
-    } else {
-      switch (pl.I) {
-        case 2: launch_dma<2, 4, EPI>(pl, p, s); break;
-        case 4: launch_dma<4, 4, EPI>(pl, p, s); break;
-        case 6: launch_dma<6, 4, EPI>(pl, p, s); break;
-        default: launch_dma<8, 4, EPI>(pl, p, s); break;
-      }
+  } else if (pl.NB == 2) {
+    switch (pl.I) {
+      case 2: launch_dma<2, 2, EPI, 4>(pl, p, s); break;
+      case 4: launch_dma<4, 2, EPI, 4>(pl, p, s); break;
+      case 6: launch_dma<6, 2, EPI, 4>(pl, p, s); break;
+      default: launch_dma<8, 2, EPI, 4>(pl, p, s); break;
     }
+  } else if (pl.nwv == 8) {
+    switch (pl.I) {
+      case 4: launch_dma<4, 4, EPI, 8>(pl, p, s); break;
+      case 6: launch_dma<6, 4, EPI, 8>(pl, p, s); break;
+      default: launch_dma<8, 4, EPI, 8>(pl, p, s); break;
+    }
+  } else {
+    launch_dma<2, 4, EPI, 4>(pl, p, s);
   }
 }
 
@@ -964,11 +967,13 @@ hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
   const GemmPlan pl = fill_params(g, &p);
   if (pl.tail_splits > 1) {
     const dim3 tg((unsigned)((pl.grid_ids - pl.tail_first) / pl.tail_splits) * (pl.I / 2) * (pl.NB / 2));
-#define CB_TAIL(I_, NB_) hipLaunchKernelGGL((swiglu_tail_kernel<I_, NB_>), tg, dim3(256), 0, s, p, pl.tiles_m, pl.tiles_n)
+#define CB_TAIL(I_, NB_, W_) hipLaunchKernelGGL((swiglu_tail_kernel<I_, NB_, W_>), tg, dim3(256), 0, s, p, pl.tiles_m, pl.tiles_n)
     if (pl.NB == 2) {
-      switch (pl.I) { case 2: CB_TAIL(2, 2); break; case 4: CB_TAIL(4, 2); break; case 6: CB_TAIL(6, 2); break; default: CB_TAIL(8, 2); break; }
+      switch (pl.I) { case 2: CB_TAIL(2, 2, 4); break; case 4: CB_TAIL(4, 2, 4); break; case 6: CB_TAIL(6, 2, 4); break; default: CB_TAIL(8, 2, 4); break; }
+    } else if (pl.nwv == 8) {
+      switch (pl.I) { case 4: CB_TAIL(4, 4, 8); break; case 6: CB_TAIL(6, 4, 8); break; default: CB_TAIL(8, 4, 8); break; }
     } else {
-      switch (pl.I) { case 2: CB_TAIL(2, 4); break; case 4: CB_TAIL(4, 4); break; case 6: CB_TAIL(6, 4); break; default: CB_TAIL(8, 4); break; }
+      CB_TAIL(2, 4, 4);
     }
 #undef CB_TAIL
     return hipGetLastError();
