@@ -235,7 +235,7 @@ def check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, tol)
 
 
 def test_workload_tiny_end_to_end(P):
-    """BASELINE workload 1 exactly: 2 layers, 4 x 128 tokens + 32, keep [512, 154], float."""
+    """The tiny float workload exactly: 2 layers, 4 x 128 tokens + 32, keep [512, 154]."""
     w = WORKLOADS["tiny"]
     announce("tiny end to end")
     layers = synth.model_weights(w.model, w.seed_weights)
