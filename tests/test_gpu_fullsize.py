@@ -119,3 +119,47 @@ def test_dense_first_layer_at_real_width_sampled(P):
     err = max_abs_rel(to_np(h_out)[rows], ref)
     print(f"dense layer 0: sampled h_out max-abs-rel {err:.2e}")
     assert err < tol
+
+
+def test_three_layer_prefill_at_real_width(P):
+    """End to end at the Mistral-7B width with reduced depth: re-alignment, a full layer 0, the
+    first check on all 3072 context rows, a second check on the survivors.  The pre-computed caches
+    are seeded random rows (an input like any other); the whole parity protocol applies."""
+    w = WORKLOADS["mistral7b"].with_layers(3)
+    model = w.model
+    announce("three-layer prefill at real width", w.n_tokens)
+    layers = [synth.layer_weights(model, l, w.seed_weights) for l in range(3)]
+    npl = np_layers(layers)
+    x = synth.hidden_inputs(w)
+    dt = synth.storage_dtype(model)
+    C, T = w.n_ctx, w.n_tokens
+    shape = (C, model.n_kv_heads, model.head_dim)
+    kpre = [synth.random_rows(C, model.kv_dim, 0.5, 8100 + l, dtype=dt).view(shape) for l in range(3)]
+    vpre = [synth.random_rows(C, model.kv_dim, 0.5, 8200 + l, dtype=dt).view(shape) for l in range(3)]
+    keep = [C, 922, 877]
+    ctx = P.cb_create(model, T)
+    kg = [torch.zeros((T,) + shape[1:], dtype=dt, device="cuda") for _ in range(3)]
+    vg = [torch.zeros_like(t) for t in kg]
+    for l in range(3):
+        kg[l][:C] = kpre[l].cuda()
+        vg[l][:C] = vpre[l].cuda()
+    out = P.cb_fuse_prefill(ctx, dev_layers(layers), x.cuda(), w.chunk_lens, w.n_suffix, kg, vg, keep,
+                            want_sel=True, want_dev=True)
+    torch.cuda.synchronize()
+    P.cb_destroy(ctx)
+    tol = TOL["bf16"]
+    sel = [s.cpu().numpy().astype(np.int64) for s in out.sel]
+    cand = np.arange(C)
+    for l in (1, 2):
+        d = out.dev[l].cpu().numpy()
+        assert np.array_equal(sel[l], cand[O.top_k_indices(d, keep[l])]), f"layer {l}"      # bit-exact selection
+        cand = sel[l]
+    ref = O.fuse_prefill(to_np(x), npl, model, w.chunk_lens, w.n_suffix, [to_np(t) for t in kpre],
+                         [to_np(t) for t in vpre], keep, forced_sel=sel, kv_round=O.round_bf16)
+    for l in range(3):
+        assert max_abs_rel(to_np(kg[l].cpu()), ref.K[l]) < tol and max_abs_rel(to_np(vg[l].cpu()), ref.V[l]) < tol
+        if l:
+            assert max_abs_rel(out.dev[l].cpu().numpy(), ref.dev[l]) < tol
+    err = max_abs_rel(to_np(out.final_hidden.cpu()), ref.final_hidden)
+    print(f"three layers at real width: final hidden max-abs-rel {err:.2e}")
+    assert err < tol
