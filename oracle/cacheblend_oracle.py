@@ -413,3 +413,52 @@ def pick_storage_device(recompute_delay_value, load_delays, costs):
         if t <= recompute_delay_value and (best < 0 or c < costs[best]):
             best = i
     return best
+
+
+# --------------------------------------------------------------------------- #
+# diagnostics (Sec. 4.1 definitions, Sec. 4.3 insight 2); analysis only
+# --------------------------------------------------------------------------- #
+def forward_attention_matrix(q, q_pos, k_cache):
+    """A [Hq, n, n_keys]: softmax of the masked scaled scores of the query rows (the "forward
+    attention matrix" of Sec. 4.1), n_keys = largest query position + 1."""
+    q = np.asarray(q, F64)
+    n, hq, dh = q.shape
+    group = hq // k_cache.shape[1]
+    q_pos = np.asarray(q_pos, dtype=np.int64)
+    n_keys = int(q_pos.max()) + 1
+    visible = np.arange(n_keys)[None, :] <= q_pos[:, None]
+    out = np.zeros((hq, n, n_keys), F64)
+    for h in range(hq):
+        sc = q[:, h, :] @ np.asarray(k_cache[:n_keys, h // group, :], F64).T / math.sqrt(dh)
+        sc = np.where(visible, sc, -np.inf)
+        sc = np.exp(sc - sc.max(axis=1, keepdims=True))
+        out[h] = sc / sc.sum(axis=1, keepdims=True)
+    return out
+
+
+def attention_deviation(a, a_full):
+    """Delta_attn(A, A_full): the L2 norm of the difference of two forward attention matrices
+    (Sec. 4.1)."""
+    d = np.asarray(a, F64) - np.asarray(a_full, F64)
+    return float(np.sqrt(np.sum(d * d)))
+
+
+def spearman_rank_correlation(x, y):
+    """Spearman's rank correlation of two score vectors (Sec. 4.3 uses it between the KV
+    deviations of the same tokens on neighbouring layers): Pearson correlation of the ranks,
+    equal values sharing the mean of their ranks."""
+    def ranks(v):
+        v = np.asarray(v, F64)
+        order = np.argsort(v, kind="stable")
+        r = np.empty(len(v), F64)
+        i = 0
+        while i < len(v):
+            j = i
+            while j + 1 < len(v) and v[order[j + 1]] == v[order[i]]:
+                j += 1
+            r[order[i:j + 1]] = 0.5 * (i + j) + 1.0
+            i = j + 1
+        return r
+    rx, ry = ranks(x), ranks(y)
+    rx, ry = rx - rx.mean(), ry - ry.mean()
+    return float(np.sum(rx * ry) / math.sqrt(np.sum(rx * rx) * np.sum(ry * ry)))

@@ -505,3 +505,63 @@ def test_controller_reaches_the_papers_conclusions():
     assert O.pick_storage_device(20.0, loads, costs) == 2
     assert O.pick_storage_device(0.1, loads, costs) == -1
     assert O.pick_storage_device(3.0, [1.0, 1.0], [2.0, 2.0]) == 0
+
+
+# --------------------------------------------------------------------------- #
+# diagnostics of Sec. 4.1 / 4.3
+# --------------------------------------------------------------------------- #
+def test_spearman_against_scipy_including_ties():
+    from scipy.stats import spearmanr
+    rng = np.random.default_rng(8)
+    for _ in range(5):
+        x = rng.standard_normal(40)
+        y = 0.5 * x + rng.standard_normal(40)
+        assert abs(O.spearman_rank_correlation(x, y) - spearmanr(x, y)[0]) < 1e-12
+    xi = rng.integers(0, 5, 60).astype(float)          # many ties
+    yi = rng.integers(0, 5, 60).astype(float)
+    assert abs(O.spearman_rank_correlation(xi, yi) - spearmanr(xi, yi)[0]) < 1e-12
+    assert abs(O.spearman_rank_correlation(x, 3 * x + 1) - 1.0) < 1e-12
+    assert abs(O.spearman_rank_correlation(x, -x) + 1.0) < 1e-12
+
+
+def test_forward_attention_matrix_rows_and_consistency_with_attention():
+    rng = np.random.default_rng(9)
+    T, hq, hkv, dh = 12, 4, 2, 8
+    k = rng.standard_normal((T, hkv, dh)); v = rng.standard_normal((T, hkv, dh))
+    pos = np.array([2, 5, 11])
+    q = rng.standard_normal((3, hq, dh))
+    a = O.forward_attention_matrix(q, pos, k)
+    assert a.shape == (hq, 3, T) and np.allclose(a.sum(axis=2), 1.0)
+    for i, p in enumerate(pos):
+        assert np.all(a[:, i, p + 1:] == 0.0)          # nothing after the query's own position
+    out = O.attention(q, pos, k, v)
+    for h in range(hq):
+        assert np.allclose(a[h] @ v[:, h // (hq // hkv), :], out[:, h, :], atol=1e-12)
+    assert O.attention_deviation(a, a) == 0.0
+    b = a.copy(); b[0, 0, 0] += 3.0; b[1, 2, 4] -= 4.0
+    assert abs(O.attention_deviation(b, a) - 5.0) < 1e-12          # 3-4-5
+
+
+def test_attention_deviation_shrinks_as_more_tokens_are_recomputed():
+    """Sec. 4.3 in spirit: recomputing the highest-deviation tokens first brings the forward
+    attention matrix that the suffix tokens see towards the full prefill's, down to zero at
+    ratio 1.  Synthetic weights have no heavy tail, so only the direction is asserted."""
+    w = Workload("diag", SMALL, (9, 8, 10, 7), 4, 0.3, 0.5, 21, 22)
+    _, layers, _, x, kpre, vpre = setup_fuse(w)
+    kf, vf, hf = O.full_prefill(x, layers, w.model)
+    last = w.model.n_layers - 1
+    spos = np.arange(w.n_ctx, w.n_tokens)
+    q = rng_queries(w, 123)                  # the same probe queries on both caches
+    a_full = O.forward_attention_matrix(q, spos, kf[last])
+    devs = []
+    for r in (0.0, 0.25, 0.5, 1.0):
+        keep = [w.n_ctx] + [int(math.ceil(r * w.n_ctx - 1e-9))] * (w.model.n_layers - 1)
+        out = O.fuse_prefill(x, layers, w.model, w.chunk_lens, w.n_suffix, kpre, vpre, keep)
+        devs.append(O.attention_deviation(O.forward_attention_matrix(q, spos, out.K[last]), a_full))
+    assert devs[-1] < 1e-9
+    assert devs[0] > devs[1] > devs[2] > devs[3]
+
+
+def rng_queries(w, seed):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((w.n_suffix, w.model.n_q_heads, w.model.head_dim))
