@@ -376,8 +376,15 @@ int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out) {
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CB_EHIP; }
   // rotary table in double precision on the host: (cos, sin)(p * theta^(-2i/dh)) (Appendix A)
   const int half = m.head_dim / 2;
-  std::vector<float2> tab((size_t)max_tokens * half);
-  std::vector<double> freq(half);
+  std::vector<float2> tab;
+  std::vector<double> freq;
+  try {
+    tab.resize((size_t)max_tokens * half);
+    freq.resize(half);
+  } catch (...) {                       // no exception may cross the C boundary
+    delete c;
+    return CB_ENOMEM;
+  }
   for (int i = 0; i < half; ++i) freq[i] = std::pow((double)m.rope_theta, -2.0 * i / m.head_dim);
   for (int p = 0; p < max_tokens; ++p)
     for (int i = 0; i < half; ++i) {
@@ -584,9 +591,13 @@ int cb_fuse_prefill(cb_ctx *c, const cb_layer_weights *layers, const void *x, co
                     void *const *v_cache_layers, const int32_t *keep_counts,
                     const int32_t *const *forced_sel, float *final_hidden, int32_t *const *sel_dump,
                     float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) {
-  return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, nullptr, nullptr, k_cache_layers,
-                      v_cache_layers, keep_counts, forced_sel, final_hidden, sel_dump, dev_dump, workspace,
-                      workspace_bytes, stream, nullptr);
+  try {
+    return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, nullptr, nullptr, k_cache_layers,
+                        v_cache_layers, keep_counts, forced_sel, final_hidden, sel_dump, dev_dump, workspace,
+                        workspace_bytes, stream, nullptr);
+  } catch (...) {                       // host bookkeeping ran out of memory
+    return CB_ENOMEM;
+  }
 }
 
 int cb_fuse_prefill_pipelined(cb_ctx *c, const cb_layer_weights *layers, const void *x,
@@ -597,9 +608,13 @@ int cb_fuse_prefill_pipelined(cb_ctx *c, const cb_layer_weights *layers, const v
                               size_t workspace_bytes, void *stream, void *copy_stream) {
   if (!k_host_layers || !v_host_layers) return CB_ENULL;
   if (stream == copy_stream) return CB_EINVAL;       // the copies must not queue behind the compute
-  return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, k_host_layers, v_host_layers,
-                      k_cache_layers, v_cache_layers, keep_counts, nullptr, final_hidden, nullptr, nullptr,
-                      workspace, workspace_bytes, stream, copy_stream);
+  try {
+    return prefill_impl(c, layers, x, chunk_lens, n_chunks, n_suffix, k_host_layers, v_host_layers,
+                        k_cache_layers, v_cache_layers, keep_counts, nullptr, final_hidden, nullptr, nullptr,
+                        workspace, workspace_bytes, stream, copy_stream);
+  } catch (...) {
+    return CB_ENOMEM;
+  }
 }
 
 size_t cb_batched_workspace_bytes(const cb_ctx *c, int32_t total_tokens) {
@@ -613,7 +628,7 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
                             const int32_t *chunk_lens, const int32_t *n_chunks, const int32_t *n_suffix,
                             void *const *k_cache_layers, void *const *v_cache_layers, int32_t cache_stride,
                             const int32_t *keep_counts, float *final_hidden, int32_t *const *sel_dump,
-                            float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) {
+                            float *const *dev_dump, void *workspace, size_t workspace_bytes, void *stream) try {
   if (!c || !layers || !x || !chunk_lens || !n_chunks || !n_suffix || !k_cache_layers || !v_cache_layers ||
       !keep_counts || !workspace)
     return CB_ENULL;
@@ -711,6 +726,8 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
     }
   }
   return CB_OK;
+} catch (...) {                 // host bookkeeping ran out of memory
+  return CB_ENOMEM;
 }
 
 int cb_first_token(cb_ctx *c, const float *final_hidden, int32_t n_suffix, const void *final_norm,
