@@ -140,12 +140,11 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //   tile        BM = 32*I rows (I = 2,4,6,8) x BN = 64*NB columns (NB = 4, or 2 when that
 //               fills the CUs better) x 64 k per stage (128-byte
 //               rows: every global request is a whole cache line)
-//   wavefronts  4 as 2 x 2, each owning (BM/2) x (BN/2) = (I/2) x NB MFMA tiles: the
-//               layout with the fewest LDS operand bytes per MFMA (LDS read bandwidth,
-//               not the matrix cores, limits narrower wavefront tiles).  With one
-//               wavefront per SIMD nothing else hides LDS latency, so the operand
-//               reads are issued by hand (inline ds_read_b128 + explicit
-//               s_waitcnt lgkmcnt) one k-step ahead of the MFMAs that use them.
+//   wavefronts  NWV = 4 as 2 x 2 (128-column tiles; two such workgroups share a CU when the
+//               rings fit twice) or NWV = 8 as 2 x 4 (256-column tiles: two wavefronts per
+//               SIMD, each (BM/2) x 64).  Operand reads are issued by hand (inline
+//               ds_read_b128 + explicit s_waitcnt lgkmcnt) one k-step ahead of the MFMAs
+//               that use them, slotted between those MFMAs.
 //   LDS rings   activation tile (BM rows x 128 bytes): 2 stages; weight tile (256 rows x
 //               128 bytes): the 3-4 stages that still fit in 160 KB -- weights stream
 //               from HBM once and need the deeper queue, activations mostly hit L2.
@@ -159,7 +158,8 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //               then every wavefront holds its last fragments of stage t in
 //               registers, so after "tile t+1 landed" (s_waitcnt vmcnt) + barrier the
 //               stage is refilled with tile t+S and the first fragments of tile t+1
-//               are requested while the last 16 MFMAs of tile t run.  The
+//               are requested while the last MFMAs of tile t run.  The loads of a tile
+//               are spread over four k-steps (no burst on the memory pipeline).  The
 //               compiler does not order LDS reads against these loads, hence the
 //               explicit waits; plain s_barrier is used because __syncthreads()
 //               would drain every outstanding load.
