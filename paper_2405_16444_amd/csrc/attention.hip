@@ -104,7 +104,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
   float row_max[NQB], row_sum[NQB];
 #pragma unroll
   for (int b = 0; b < NQB; ++b) {
-    row_max[b] = kNegBig;
+    row_max[b] = -INFINITY;
     row_sum[b] = 0.f;
 #pragma unroll
     for (int d = 0; d < DB; ++d)
@@ -203,14 +203,16 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
       const bool diag = t0 + BKV - 1 > wave_min_pos;     // wave-uniform: some key of the tile is masked
 #pragma unroll
       for (int b = 0; b < NQB; ++b) {
-        float mx = kNegBig;
+        // masked scores are -inf; a query that has seen no key yet (possible inside a later piece of
+        // the key range, or for the padding lanes) keeps max = -inf and gets p = 0 everywhere
+        float mx = -INFINITY;
         if (diag) {
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               const int key = t0 + kb * 32 + (i >> 2) * 8 + h * 4 + (i & 3);
-              sacc[b][kb][i] = key <= my_pos[b] ? sacc[b][kb][i] : kNegBig;
+              sacc[b][kb][i] = key <= my_pos[b] ? sacc[b][kb][i] : -INFINITY;
             }
         }
 #pragma unroll
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
           for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[b][kb][i]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float new_max = fmaxf(row_max[b], mx);
-        const float neg_mc = -new_max * scale_log2e;
+        const float neg_mc = new_max == -INFINITY ? 0.f : -new_max * scale_log2e;
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
         // the accumulators only need rescaling when some query's running max moved, which
         // becomes rare after the first tiles
         if (__any(new_max > row_max[b])) {
-          const float alpha = __builtin_amdgcn_exp2f((row_max[b] - new_max) * scale_log2e);
+          const float alpha = new_max > row_max[b] ? __builtin_amdgcn_exp2f((row_max[b] - new_max) * scale_log2e) : 1.f;
           row_sum[b] *= alpha;
 #pragma unroll
           for (int d = 0; d < DB; ++d)
