@@ -227,7 +227,12 @@ def check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, tol)
                          forced_sel=sel_gpu, kv_round=rnd)
     for l in range(w.model.n_layers):
         if keep[l] < (w.n_ctx if l == 0 else keep[l - 1]):
-            assert max_abs_rel(out.dev[l].cpu().numpy(), ref.dev[l]) < tol, f"dev layer {l}"
+            got = out.dev[l].cpu().numpy()
+            if ref.dev[l].size and ref.dev[l].max() < 1e-9:
+                # every candidate sits in the first chunk (a prefix): the deviation is rounding noise
+                assert got.max() < (1e-6 if w.model.dtype == "f32" else 0.5), f"dev layer {l}"
+            else:
+                assert max_abs_rel(got, ref.dev[l]) < tol, f"dev layer {l}"
         assert max_abs_rel(to_np(kg[l].cpu()), ref.K[l]) < tol, f"K layer {l}"
         assert max_abs_rel(to_np(vg[l].cpu()), ref.V[l]) < tol, f"V layer {l}"
     assert max_abs_rel(to_np(out.final_hidden.cpu()), ref.final_hidden) < tol

@@ -80,3 +80,40 @@ def test_rows_with_no_visible_key_in_a_later_piece_of_the_key_range(P, dh, hq, h
     assert bool(torch.isfinite(h_out).all())
     h_ref, pos_ref, _, ko, vo = oracle_layer(model, lw, h, pos, kc, vc, n_suffix, k, None)
     assert max_abs_rel(to_np(h_out), h_ref) < TOL["bf16"]
+
+
+def prefill_cases():
+    rng = np.random.default_rng(77001)
+    out = []
+    names = ["f32", "bf16", "bf16_g7", "bf16_dh64"]
+    for i in range(14):
+        n_layers = int(rng.integers(2, 4))    # deeper stacks of these wide-weight test models leave the bf16 budget
+        n_chunks = int(rng.integers(1, 10))
+        lens = tuple(int(v) for v in rng.integers(1, 150, n_chunks))
+        n_suffix = int(rng.integers(0, 34))
+        fr = np.sort(rng.random(n_layers - 1))[::-1]
+        if i % 4 == 1:
+            fr[-1] = 0.0                                  # ends with nothing kept but the suffix
+        if i % 4 == 2:
+            fr[:] = fr[0]                                 # one selection, then no further check
+        if i % 5 == 3:
+            fr[0] = 1.0                                   # the first "check" keeps everything
+        out.append((i, names[i % 4], n_layers, lens, n_suffix, tuple(float(v) for v in fr)))
+    return out
+
+
+@pytest.mark.parametrize("case", prefill_cases(), ids=lambda c: f"{c[0]}-{c[1]}-L{c[2]}-c{len(c[3])}-s{c[4]}")
+def test_prefill_sweep(P, case):
+    from dataclasses import replace
+    from test_gpu_parity import MODELS, check_prefill_against_oracle, e2e_case, run_prefill
+    i, name, n_layers, lens, n_suffix, fr = case
+    if n_suffix == 0 and fr[-1] == 0.0:
+        n_suffix = 1                                      # keep at least one row alive to the end
+    model = replace(MODELS[name], n_layers=n_layers)
+    announce("prefill sweep", case)
+    w, layers, x, npl, xn, kpre, vpre = e2e_case(model, lens, n_suffix, seed=900 + i)
+    keep = [w.n_ctx]
+    for f in fr:
+        keep.append(min(keep[-1], int(np.ceil(f * w.n_ctx))))
+    out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, keep)
+    check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, TOL[model.dtype])
