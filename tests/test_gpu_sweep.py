@@ -117,3 +117,48 @@ def test_prefill_sweep(P, case):
         keep.append(min(keep[-1], int(np.ceil(f * w.n_ctx))))
     out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, keep)
     check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, TOL[model.dtype])
+
+
+def wide_cases():
+    rng = np.random.default_rng(4242)
+    geoms = [(1024, 8, 2, 128, 2048), (1024, 16, 2, 64, 4096), (1536, 12, 4, 128, 3072), (1024, 8, 1, 128, 2816),
+             (2048, 16, 2, 128, 1024)]
+    out = []
+    for i in range(15):
+        d, hq, hkv, dh, f = geoms[i % len(geoms)]
+        n_rows = int(rng.choice([97, 200, 257, 390, 513, 700, 769, 1025, 1300]))
+        n_suffix = int(rng.integers(0, 65))
+        n_suffix = min(n_suffix, n_rows)
+        n_cand = n_rows - n_suffix
+        mode = i % 3
+        k = n_cand if mode == 0 else int(n_cand * (0.93 if mode == 1 else 0.4))
+        n_tokens = n_rows + int(rng.integers(0, 2500))
+        out.append((i, d, hq, hkv, dh, f, n_tokens, n_rows, n_suffix, k))
+    return out
+
+
+@pytest.mark.parametrize("case", wide_cases(), ids=lambda c: f"{c[0]}-d{c[1]}-h{c[2]}/{c[3]}x{c[4]}-f{c[5]}-T{c[6]}-r{c[7]}-s{c[8]}-k{c[9]}")
+def test_layer_sweep_wider_models(P, case):
+    """Widths at which the big-tile GEMM variants, their K splits and shared tail tiles, and the
+    different key-range splits of the attention kernel all come into play."""
+    i, d, hq, hkv, dh, f, n_tokens, n_rows, n_suffix, k = case
+    model = ModelShape(1, d, hq, hkv, dh, f, 1e-5, 1e4, "bf16")
+    announce("wide sweep", case)
+    lw, h, pos, kc, vc = layer_case(model, n_tokens, n_rows, n_suffix, seed=6000 + i, std=0.04)
+    n_cand = n_rows - n_suffix
+    check = k < n_cand
+    h_out, pos_out, dev, kg, vg = run_layer_both(P, model, lw, h, pos, kc, vc, n_suffix, k, want_dev=check)
+    tol = TOL["bf16"]
+    forced = None
+    if check:
+        sel_pos = pos.numpy()[:n_cand][O.top_k_indices(dev.numpy(), k)]
+        assert np.array_equal(pos_out.numpy()[:k], sel_pos)
+        forced = sel_pos
+    h_ref, pos_ref, dev_ref, ko, vo = oracle_layer(model, lw, h, pos, kc, vc, n_suffix, k, forced)
+    assert np.array_equal(pos_out.numpy(), pos_ref)
+    if check:
+        assert max_abs_rel(dev.numpy(), dev_ref) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    untouched = np.setdiff1d(np.arange(n_tokens), pos_ref)
+    assert torch.equal(kg[untouched], kc[untouched]) and torch.equal(vg[untouched], vc[untouched])
+    assert max_abs_rel(to_np(h_out), h_ref) < tol
