@@ -762,7 +762,7 @@ static int pick_row_blocks(int M) {
 struct DmaShape { int I, NB; double t_full; };
 // Whole-prefill timings decided the candidate set: adding the 8x2, 4x4 and 6x4 tiles changed
 // nothing beyond noise, and 64-row tiles lost wherever more than 64 rows exist.
-static const DmaShape kDmaShapes[] = {{2, 2, 1.00}, {4, 2, 1.45}, {6, 2, 1.15}, {8, 4, 2.60}};
+static const DmaShape kDmaShapes[] = {{2, 2, 1.00}, {4, 2, 1.45}, {6, 2, 1.15}, {8, 4, 2.30}};
 
 static void pick_dma_plan(int M, int N, int K, GemmPlan *pl) {
   const int k_tiles = K / DMA_BK;
