@@ -172,7 +172,7 @@ int cb_fuse_prefill_pipelined(cb_ctx *ctx, const cb_layer_weights *layers, const
                               const int32_t *keep_counts, float *final_hidden, void *workspace,
                               size_t workspace_bytes, void *stream, void *copy_stream);
 
-/* Several requests in one pass (Sec. 7 sensitivity analysis, "varying batch size"): the projections and the MLP run on
+/* Several requests in one pass (Sec. 7 sensitivity analysis, the batch-size paragraph): the projections and the MLP run on
  * the stacked rows of all requests, selection and attention per request.  Request b contributes
  * n_chunks[b] chunks and n_suffix[b] query tokens; T_b = its context + suffix length.
  *   x             : T [sum_b T_b, d], request after request, each: context chunks then suffix

@@ -7,7 +7,7 @@ library; only tests, the smoke check and the bench's `cpu_baseline` leg may call
 it.
 
 What the paper fixes and where:
-  * prefill = per-layer Q/K/V, masked softmax attention, "further layers"
+  * prefill = per-layer Q/K/V, masked softmax attention, further layers
     producing the next layer's input                              (Sec. 2)
   * pre-computed caches: each chunk prefilled alone as a prefix   (Sec. 4.1)
   * positional recovery of cached keys by one more rotation       (Sec. 4.3
@@ -142,7 +142,7 @@ def silu(z):
 
 def finish_block(h_rows, attn_out, lw, m):
     """Everything after attention: output projection + residual, then the
-    SwiGLU MLP + residual ("multiple neural layers", Sec. 2)."""
+    SwiGLU MLP + residual (the further per-layer networks of Sec. 2)."""
     n = h_rows.shape[0]
     h = h_rows + attn_out.reshape(n, m.n_q_heads * m.head_dim) @ lw["wo"].T
     y = rms_norm(h, lw["mlp_norm"], m.rms_eps)
@@ -231,7 +231,7 @@ def realign_keys(k_pre, chunk_lens, m, kv_round=identity):
 # --------------------------------------------------------------------------- #
 def kv_deviation(k_new, v_new, k_old, v_old):
     """Per-token deviation between two KV rows: sum of squared differences over
-    every kv head and channel of K and of V (Sec. 4.1 'absolute difference';
+    every kv head and channel of K and of V (Sec. 4.1 defines it as a difference of the two;
     the norm is this build's reading)."""
     dk = np.asarray(k_new, F64) - np.asarray(k_old, F64)
     dv = np.asarray(v_new, F64) - np.asarray(v_old, F64)

@@ -188,7 +188,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   const int32_t *sel_rows = nullptr;
   bool q_all = false;
   if (check) {
-    // K/V of every row that reached this layer (Sec. 6: "newly computed KV")
+    // K/V of every row that reached this layer (Sec. 6: the KV computed anew on this layer)
     // When nearly every candidate survives (gradual filtering), Q is projected for all candidates
     // in the same launch and attention picks the kept rows through sel_rows; otherwise Q is
     // projected after the selection, for the kept rows only.

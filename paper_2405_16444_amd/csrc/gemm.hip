@@ -1,5 +1,5 @@
 // Projections of the selectively recomputed rows (paper Sec. 4.2: Q/K/V of the
-// selected tokens, then "the same attention module" and the rest of the layer).
+// selected tokens, then the ordinary attention and the rest of the layer).
 // C[M, N] = A[M, K] * W[N, K]^T with both operands K-contiguous.
 //
 // bf16 storage: v_mfma_f32_32x32x16_bf16 with float accumulation.  The main kernel
