@@ -375,6 +375,10 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) rd[ks] = (lane & 31) * 128 + (((2 * ks + h) ^ sw) << 4);
     const int a_off = (wm * IH * 32) * 128, b_off = (wn * (BN / WN)) * 128;
+    int blk_ok = 0;                                    // bit i: row block i of this wavefront holds a real row
+#pragma unroll
+    for (int i = 0; i < IH; ++i) blk_ok |= (m0 + (wm * IH + i) * 32 < p.M) << i;
+    blk_ok = __builtin_amdgcn_readfirstlane(blk_ok);
     bf16x8 fa[2][IH], fb[2][NBW];
     constexpr int NM = IH * NBW;                       // MFMAs per k-step per wavefront
     constexpr int NL = LA + LW;                        // loads per tile per lane
@@ -414,7 +418,9 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
       const unsigned base_a = lds0 + (tn % DMA_SA) * A_STAGE + a_off + rd[ksn];
 #pragma unroll
       for (int j = 0; j < NSLOT; ++j) {
-        if (j < NM)
+        // a 32-row block that lies wholly past the last row (only in the last row tile) is skipped:
+        // the wavefront sharing the SIMD gets the matrix core instead
+        if (j < NM && ((blk_ok >> (j / NBW)) & 1))
           acc[j / NBW][j % NBW] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / NBW], fb[buf][j % NBW],
                                                                          acc[j / NBW][j % NBW], 0, 0, 0);
         // global loads q0 .. q1-1 of tile tl, spread evenly over the slots of this k-step
