@@ -96,6 +96,37 @@ def test_selective_layer_at_real_width(P, name, n_tokens, n_rows, n_suffix, k_ke
     assert err < tol
 
 
+def _bench_schedule_shapes():
+    """(layer, rows in, kept) of layers 1..31 of the default benchmark request: the rows that enter
+    a layer are the context rows the layer before kept, plus the 64 query rows."""
+    w = WORKLOADS["mistral7b"]
+    keep = O.default_schedule(w.model.n_layers, w.n_ctx, w.ratio, w.ratio_first)
+    return [(l, int(keep[l - 1]) + w.n_suffix, int(keep[l])) for l in range(1, w.model.n_layers)]
+
+
+@pytest.mark.parametrize("layer,n_rows,k_keep", _bench_schedule_shapes())
+def test_every_layer_shape_of_the_benchmark_schedule(P, layer, n_rows, k_keep):
+    """Each GEMM, top-k and attention launch shape of the request bench.py times (the tile plan
+    changes with the row count from layer to layer), one layer at a time with inputs of its own
+    so that no error is carried from layer to layer."""
+    w = WORKLOADS["mistral7b"]
+    model = replace(w.model, n_layers=1)
+    announce("benchmark schedule layer", layer, n_rows, k_keep)
+    lw, nlw = full_layer("mistral7b")
+    h, pos, kc, vc = case(model, w.n_tokens, n_rows, w.n_suffix, seed=9000 + layer)
+    h_out, pos_out, dev, kg, vg = run_gpu(P, model, lw, h, pos, kc, vc, w.n_suffix, k_keep, True)
+    tol = TOL["bf16"]
+    n_cand = n_rows - w.n_suffix
+    sel_pos = pos.numpy()[:n_cand][O.top_k_indices(dev.numpy(), k_keep)]
+    assert np.array_equal(pos_out.numpy()[:k_keep], sel_pos)
+    ko, vo = to_np(kc), to_np(vc)
+    h_ref, pos_ref, dev_ref, _ = O.fuse_layer(nlw, model, to_np(h), pos.numpy(), w.n_suffix, ko, vo, k_keep,
+                                              forced_sel=sel_pos, kv_round=O.round_bf16)
+    assert max_abs_rel(dev.numpy(), dev_ref) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    assert max_abs_rel(to_np(h_out), h_ref) < tol
+
+
 def test_dense_first_layer_at_real_width_sampled(P):
     """Layer 0 of the Mistral-7B-shaped workload: all 3136 rows, no check.  K/V rows are compared
     in full; the layer output on 48 sampled rows."""
