@@ -89,23 +89,38 @@ def rope_frequencies(head_dim, theta):
     return theta ** (-2.0 * i / head_dim)
 
 
-def rope(v, pos, theta):
+def rope(v, pos, theta, layout="adjacent"):
     """Apply the rotary matrix R_{Theta,pos} of Appendix A to every head.
 
     v [n, H, dh]; pos [n].  The matrix is block diagonal with 2x2 blocks acting
     on the adjacent pair (2i, 2i+1):
         [cos p*th_i  -sin p*th_i] [v_2i  ]
         [sin p*th_i   cos p*th_i] [v_2i+1]
+    layout "half" is the same matrix with the channels of a head renumbered so
+    that block i acts on the pair (i, i + dh/2) -- the order in which widely
+    used checkpoints store their query/key projections.  The paper defines
+    only the adjacent order; the other one is this renumbering and nothing else.
     """
     v = np.asarray(v, F64)
     n, _, dh = v.shape
     ang = np.asarray(pos, F64).reshape(n, 1, 1) * rope_frequencies(dh, theta).reshape(1, 1, -1)
     c, s = np.cos(ang), np.sin(ang)
-    even, odd = v[..., 0::2], v[..., 1::2]
+    if layout == "adjacent":
+        first, second = (slice(0, None, 2), slice(1, None, 2))
+    elif layout == "half":
+        first, second = (slice(0, dh // 2), slice(dh // 2, None))
+    else:
+        raise ValueError(f"unknown rotary layout {layout!r}")
+    a, b = v[..., first], v[..., second]
     out = np.empty_like(v)
-    out[..., 0::2] = even * c - odd * s
-    out[..., 1::2] = even * s + odd * c
+    out[..., first] = a * c - b * s
+    out[..., second] = a * s + b * c
     return out
+
+
+def rope_layout(m):
+    """Channel order of the rotary pairs of a model description ("adjacent" unless it says otherwise)."""
+    return getattr(m, "rope_layout", "adjacent")
 
 
 def attention(q, q_pos, k_cache, v_cache):
@@ -153,14 +168,14 @@ def project_kv(h_rows, pos, lw, m):
     """K (rotated to `pos`) and V of some rows; also returns the normed input."""
     n = h_rows.shape[0]
     x = rms_norm(h_rows, lw["attn_norm"], m.rms_eps)
-    k = rope((x @ lw["wk"].T).reshape(n, m.n_kv_heads, m.head_dim), pos, m.rope_theta)
+    k = rope((x @ lw["wk"].T).reshape(n, m.n_kv_heads, m.head_dim), pos, m.rope_theta, rope_layout(m))
     v = (x @ lw["wv"].T).reshape(n, m.n_kv_heads, m.head_dim)
     return x, k, v
 
 
 def project_q(x_rows, pos, lw, m):
     n = x_rows.shape[0]
-    return rope((x_rows @ lw["wq"].T).reshape(n, m.n_q_heads, m.head_dim), pos, m.rope_theta)
+    return rope((x_rows @ lw["wq"].T).reshape(n, m.n_q_heads, m.head_dim), pos, m.rope_theta, rope_layout(m))
 
 
 def as_f64_weights(lw):
@@ -222,7 +237,7 @@ def realign_keys(k_pre, chunk_lens, m, kv_round=identity):
     out = np.array(k_pre, dtype=F64, copy=True)
     for c in range(1, len(chunk_lens)):
         a, b = off[c], off[c + 1]
-        out[a:b] = kv_round(rope(out[a:b], np.full(b - a, off[c]), m.rope_theta))
+        out[a:b] = kv_round(rope(out[a:b], np.full(b - a, off[c]), m.rope_theta, rope_layout(m)))
     return out
 
 

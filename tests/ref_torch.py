@@ -16,6 +16,17 @@ def rope_complex(v, pos, theta):
     return torch.view_as_real(vc * rot).reshape(n, h, dh)
 
 
+def rope_rotate_half(v, pos, theta):
+    """The other common statement of the rotary embedding: x * cos + swap(x) * sin, with
+    swap(x) = concat(-second half, first half) and the dh/2 angles repeated for both halves."""
+    n, h, dh = v.shape
+    freqs = theta ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh)
+    ang = pos.to(torch.float64)[:, None] * freqs[None, :]
+    ang = torch.cat([ang, ang], dim=-1)[:, None, :]
+    swapped = torch.cat([-v[..., dh // 2:], v[..., :dh // 2]], dim=-1)
+    return v * torch.cos(ang) + swapped * torch.sin(ang)
+
+
 def layer_forward(h, lw, m, pos):
     n = h.shape[0]
     x = F.rms_norm(h, (m.d_model,), lw["attn_norm"], m.rms_eps)

@@ -89,6 +89,58 @@ def test_realigned_keys_equal_keys_computed_at_new_positions():
     assert np.array_equal(re[:lens[0]], kpre[0][:lens[0]])
 
 
+def half_order(dh):
+    """Position j of the half-split order holds channel half_order[j] of the adjacent order."""
+    return np.concatenate([np.arange(0, dh, 2), np.arange(1, dh, 2)])
+
+
+def test_half_split_rope_is_the_paper_rotation_with_channels_renumbered():
+    rng = np.random.default_rng(21)
+    v = rng.standard_normal((7, 3, 16))
+    pos = np.array([0, 1, 2, 33, 1000, 4095, 32767])
+    perm = half_order(16)
+    np.testing.assert_allclose(O.rope(v[..., perm], pos, 1e6, "half"), O.rope(v, pos, 1e6)[..., perm],
+                               rtol=0, atol=1e-15)
+    # and against the concat / swap statement of it, written with torch ops
+    ref = ref_torch.rope_rotate_half(torch.from_numpy(v), torch.from_numpy(pos), 1e6).numpy()
+    np.testing.assert_allclose(O.rope(v, pos, 1e6, "half"), ref, rtol=0, atol=1e-12)
+    # the two orders are different functions of the same vector
+    assert np.abs(O.rope(v, pos, 1e6, "half") - O.rope(v, pos, 1e6)).max() > 0.1
+    with pytest.raises(ValueError):
+        O.rope(v, pos, 1e6, "interleaved")
+
+
+def test_half_split_model_equals_adjacent_model_with_renumbered_projections():
+    """Renumbering the output channels of W_q and W_k inside every head turns an adjacent-order
+    model into a half-split one: scores, hence hidden states, V caches, deviations up to rounding
+    and selections are the same, and the K caches are the renumbered K caches -- through
+    re-alignment, selection and recompute alike."""
+    layers, npl, x, xn = make(SMALL_W, std=0.3)
+    m = SMALL
+    mh = replace(m, rope_layout="half")
+    perm = half_order(m.head_dim)
+    rows_q = (np.arange(m.n_q_heads)[:, None] * m.head_dim + perm[None, :]).ravel()
+    rows_k = (np.arange(m.n_kv_heads)[:, None] * m.head_dim + perm[None, :]).ravel()
+    nph = [dict(lw, wq=lw["wq"][rows_q], wk=lw["wk"][rows_k]) for lw in npl]
+    C = SMALL_W.n_ctx
+    keep = [C, 9, 5]
+    outs = []
+    for mm, ll in ((m, npl), (mh, nph)):
+        kpre, vpre = O.chunk_prefill(xn[:C], SMALL_W.chunk_lens, ll, mm)
+        outs.append((kpre, O.fuse_prefill(xn, ll, mm, SMALL_W.chunk_lens, SMALL_W.n_suffix, kpre, vpre, keep)))
+    (kpa, a), (kph, h) = outs
+    for l in range(m.n_layers):
+        np.testing.assert_allclose(kph[l], kpa[l][..., perm], atol=1e-12)
+        np.testing.assert_allclose(h.K[l], a.K[l][..., perm], atol=1e-11)
+        np.testing.assert_allclose(h.V[l], a.V[l], atol=1e-11)
+        assert np.array_equal(h.sel[l], a.sel[l])
+    np.testing.assert_allclose(h.final_hidden, a.final_hidden, atol=1e-11)
+    # the layout is really in play: an adjacent-order run on the renumbered weights differs
+    kpre, vpre = O.chunk_prefill(xn[:C], SMALL_W.chunk_lens, nph, m)
+    wrong = O.fuse_prefill(xn, nph, m, SMALL_W.chunk_lens, SMALL_W.n_suffix, kpre, vpre, keep)
+    assert np.abs(wrong.final_hidden - a.final_hidden).max() > 1e-3
+
+
 # ------------------------------------------------------- block pieces -------
 def test_rmsnorm_silu_bf16_against_torch():
     rng = np.random.default_rng(3)
