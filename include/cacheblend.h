@@ -49,12 +49,19 @@ typedef enum {
 
 typedef enum { CB_F32 = 0, CB_BF16 = 1 } cb_dtype;
 
-/* Decoder geometry (RMSNorm, grouped-query attention, rotary embedding on
- * adjacent channel pairs as in Appendix A, SwiGLU MLP, no biases). */
+/* Which two channels of a head one 2x2 block of the rotary matrix (Appendix A) acts on:
+ * the adjacent pair (2i, 2i+1), as the paper writes it, or (i, i + head_dim/2), the
+ * order in which many checkpoints store their query/key projections.  Same matrix,
+ * channels renumbered; the caches a caller hands in must be in the same order. */
+typedef enum { CB_ROPE_ADJACENT = 0, CB_ROPE_HALF = 1 } cb_rope_layout;
+
+/* Decoder geometry (RMSNorm, grouped-query attention, rotary embedding as in
+ * Appendix A, SwiGLU MLP, no biases). */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
   float rms_eps, rope_theta;
-  int32_t dtype; /* cb_dtype */
+  int32_t dtype;       /* cb_dtype */
+  int32_t rope_layout; /* cb_rope_layout */
 } cb_model_desc;
 
 /* One layer's weights (all of storage type T). */

@@ -27,7 +27,11 @@ class CacheBlendError(RuntimeError):
 class _ModelDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
+                ("rope_layout", C.c_int32)]
+
+
+_ROPE_LAYOUTS = {"adjacent": 0, "half": 1}
 
 
 _WEIGHT_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate", "w_up", "w_down")
@@ -141,7 +145,8 @@ class Context:
         self.dtype_code = _dtype_code(model)
         self.dtype = _torch_dtype(self.dtype_code)
         desc = _ModelDesc(model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads,
-                          model.head_dim, model.d_ff, model.rms_eps, model.rope_theta, self.dtype_code)
+                          model.head_dim, model.d_ff, model.rms_eps, model.rope_theta, self.dtype_code,
+                          _ROPE_LAYOUTS[getattr(model, "rope_layout", "adjacent")])
         handle = C.c_void_p()
         _check(_lib.cb_create(C.byref(desc), self.max_tokens, C.byref(handle)), "cb_create")
         self._h = handle

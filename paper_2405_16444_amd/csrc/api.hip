@@ -87,9 +87,10 @@ size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
   // the split decision depends on M through the tile count only; tiles are multiples of 32 rows
   for (int M = 32;; M += 32) {
     const int mm = std::min(M, max_rows);
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, 2 * kv_dim, d));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim, d));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim + 2 * kv_dim, d));
+    const int rh = m.rope_layout == CB_ROPE_HALF;
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, 2 * kv_dim, d, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim, d, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim + 2 * kv_dim, d, rh, m.head_dim));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, q_dim));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, m.d_ff));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, mm, m.d_ff, d));
@@ -183,7 +184,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     CB_HIP(launch_rmsnorm(dt, h_in, w->attn_norm, ws.xn, n, d, m.rms_eps, s));
   }
   GemmArgs g = {};
-  g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim;
+  g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim; g.rope_half = m.rope_layout == CB_ROPE_HALF;
   g.partial = ws.partial; g.partial_floats = ws.partial_floats;
   const int32_t *sel_rows = nullptr;
   bool q_all = false;
@@ -364,6 +365,7 @@ int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out) {
       max_tokens < 1 || max_tokens > (1 << 24) || !(m.rms_eps > 0.f) || !(m.rope_theta > 0.f))
     return CB_EINVAL;
   if (m.dtype != CB_F32 && m.dtype != CB_BF16) return CB_EINVAL;
+  if (m.rope_layout != CB_ROPE_ADJACENT && m.rope_layout != CB_ROPE_HALF) return CB_EINVAL;
   if (m.head_dim != 64 && m.head_dim != 128) return CB_EUNSUPPORTED;
   if (m.n_q_heads % m.n_kv_heads != 0) return CB_EUNSUPPORTED;
   if (m.d_model % 8 != 0 || m.d_ff % 8 != 0) return CB_EUNSUPPORTED;  // 16-byte operand vectors
@@ -461,7 +463,7 @@ int cb_realign_rope(cb_ctx *c, void *const *k_cache_layers, int32_t layer_begin,
                        (double)(chunk_offsets[n_chunks] - chunk_offsets[1]) * kv_dim * esize(c);
   ProfScope ps(c, s, CB_PROF_REALIGN, 0, moved);
   CB_HIP(launch_realign(c->m.dtype, k_cache_layers + layer_begin, layer_end - layer_begin, chunk_offsets,
-                        n_chunks, kv_dim, c->m.head_dim, c->rope_tab, s));
+                        n_chunks, kv_dim, c->m.head_dim, c->m.rope_layout == CB_ROPE_HALF, c->rope_tab, s));
   return CB_OK;
 }
 

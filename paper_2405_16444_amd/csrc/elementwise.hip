@@ -63,8 +63,59 @@ __global__ __launch_bounds__(256) void realign_kernel(RealignArgs a, int kv_dim,
   }
 }
 
+// Same rotation for heads stored in the (i, i + head_dim/2) order: a work item is one 16-byte
+// vector of the first half of a head together with the vector head_dim/2 channels further on.
+template <typename T>
+__global__ __launch_bounds__(256) void realign_half_kernel(RealignArgs a, int kv_dim, int head_dim,
+                                                           const float2 *__restrict__ rope_tab) {
+  using V = Vec16<T>;
+  const int c = blockIdx.y;
+  const int begin = a.off[c], end = a.off[c + 1];
+  const int tok0 = begin + blockIdx.x * kRealignTok;
+  if (tok0 >= end) return;
+  const int ntok = min(kRealignTok, end - tok0);
+  const int h = head_dim / 2;
+  const int vec_per_row = kv_dim / V::N, vec_per_half = h / V::N;
+  const int items_per_row = vec_per_row / 2;
+  const int total = ntok * items_per_row;
+  V *base = reinterpret_cast<V *>(reinterpret_cast<T *>(a.layer[blockIdx.z]) + (size_t)tok0 * kv_dim);
+  const float2 *tab = rope_tab + (size_t)begin * h;
+  constexpr int U = 2;
+  for (int i0 = threadIdx.x; i0 < total; i0 += 256 * U) {
+    V lo[U], hi[U];
+    int at[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = i0 + u * 256;
+      if (i < total) {
+        const int row = i / items_per_row, j = i % items_per_row;
+        at[u] = row * vec_per_row + (j / vec_per_half) * (2 * vec_per_half) + j % vec_per_half;
+        lo[u] = base[at[u]];
+        hi[u] = base[at[u] + vec_per_half];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = i0 + u * 256;
+      if (i < total) {
+        const int e0 = ((i % items_per_row) % vec_per_half) * V::N;   // first rotary block of this vector
+        V olo, ohi;
+#pragma unroll
+        for (int j = 0; j < V::N; ++j) {
+          const float2 cs = tab[e0 + j];
+          const float x0 = lo[u].get(j), x1 = hi[u].get(j);
+          olo.set(j, x0 * cs.x - x1 * cs.y);
+          ohi.set(j, x0 * cs.y + x1 * cs.x);
+        }
+        base[at[u]] = olo;
+        base[at[u] + vec_per_half] = ohi;
+      }
+    }
+  }
+}
+
 hipError_t launch_realign(int dtype, void *const *k_layers, int n_layers, const int32_t *offs,
-                          int n_chunks, int kv_dim, int head_dim, const float2 *rope_tab,
+                          int n_chunks, int kv_dim, int head_dim, int rope_half, const float2 *rope_tab,
                           hipStream_t s) {
   for (int l0 = 0; l0 < n_layers; l0 += kRealignLayers) {
     int nl = std::min(kRealignLayers, n_layers - l0);
@@ -77,10 +128,16 @@ hipError_t launch_realign(int dtype, void *const *k_layers, int n_layers, const 
       for (int i = 0; i < nc; ++i) maxlen = std::max(maxlen, a.off[i + 1] - a.off[i]);
       if (maxlen <= 0) continue;
       dim3 grid((maxlen + kRealignTok - 1) / kRealignTok, nc, nl);
-      if (dtype == 0)
+      if (rope_half) {
+        if (dtype == 0)
+          hipLaunchKernelGGL(realign_half_kernel<float>, grid, dim3(256), 0, s, a, kv_dim, head_dim, rope_tab);
+        else
+          hipLaunchKernelGGL(realign_half_kernel<bf16>, grid, dim3(256), 0, s, a, kv_dim, head_dim, rope_tab);
+      } else if (dtype == 0) {
         hipLaunchKernelGGL(realign_kernel<float>, grid, dim3(256), 0, s, a, kv_dim, head_dim, rope_tab);
-      else
+      } else {
         hipLaunchKernelGGL(realign_kernel<bf16>, grid, dim3(256), 0, s, a, kv_dim, head_dim, rope_tab);
+      }
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }

@@ -39,6 +39,8 @@ struct GemmParams {
   const float2 *rope_tab;
   const int32_t *row_pos;
   int head_dim;
+  int rope_half;        // rotary pairs (i, i + head_dim/2) instead of (2i, 2i+1)
+  int raw_partial;      // the main kernel only parks its sums in `partial`; the reduce launch applies the epilogue
   float *out_f32;
   const float *resid;
   const int32_t *resid_rows;
@@ -74,8 +76,16 @@ template <> __device__ __forceinline__ void store4<bf16>(bf16 *d, float a, float
   *reinterpret_cast<bf16x4 *>(d) = v;
 }
 
+// Column offset from an output column to the channel it forms a rotary pair with when heads are in
+// the (i, i + head_dim/2) order.  Segments are whole heads, so gc % head_dim is the channel.
+__device__ __forceinline__ int rope_partner_offset(const GemmParams &p, int gc) {
+  const int half = p.head_dim / 2;
+  return gc % p.head_dim < half ? half : -half;
+}
+
 // One group of 4 adjacent output columns (gc .. gc+3) of logical row gr.
-// v: accumulated values; u: the matching "up" values (EPI_SWIGLU only).
+// v: accumulated values; u: EPI_SWIGLU: the matching "up" values; EPI_SEG with p.rope_half: the
+// values of columns gc + rope_partner_offset .. + 3.
 template <typename T, int EPI>
 __device__ __forceinline__ void apply_epilogue(float4 v, float4 u, int gr, int gc, const GemmParams &p) {
   if (EPI == EPI_SEG) {
@@ -83,7 +93,25 @@ __device__ __forceinline__ void apply_epilogue(float4 v, float4 u, int gr, int g
     if (p.n_seg > 1 && gc >= p.nb[1]) s = 1;
     if (p.n_seg > 2 && gc >= p.nb[2]) s = 2;
     const int lc = gc - p.nb[s];
-    if (p.rope[s]) {
+    if (p.rope[s] && p.rope_half) {
+      const int half = p.head_dim / 2, ch = lc % p.head_dim;
+      const bool first = ch < half;
+      const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (first ? ch : ch - half);
+      const float2 c0 = t[0], c1 = t[1], c2 = t[2], c3 = t[3];
+      float4 o;
+      if (first) {          // x0' = x0 cos - x1 sin, the partner holds x1
+        o.x = v.x * c0.x - u.x * c0.y;
+        o.y = v.y * c1.x - u.y * c1.y;
+        o.z = v.z * c2.x - u.z * c2.y;
+        o.w = v.w * c3.x - u.w * c3.y;
+      } else {              // x1' = x0 sin + x1 cos, the partner holds x0
+        o.x = u.x * c0.y + v.x * c0.x;
+        o.y = u.y * c1.y + v.y * c1.x;
+        o.z = u.z * c2.y + v.z * c2.x;
+        o.w = u.w * c3.y + v.w * c3.x;
+      }
+      v = o;
+    } else if (p.rope[s]) {
       const int half = p.head_dim / 2;
       const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (lc % p.head_dim) / 2;
       const float2 c0 = t[0], c1 = t[1];
@@ -125,11 +153,14 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
     const int gr = m0 + r, gc = n0 + c;
     if (gr >= p.M || gc >= p.N) continue;
     const float4 v = *reinterpret_cast<const float4 *>(sC + r * pitch + c);
-    if (EPI != EPI_SWIGLU && p.splits > 1) {
+    if (EPI != EPI_SWIGLU && (p.splits > 1 || p.raw_partial)) {
       *reinterpret_cast<float4 *>(p.partial + ((size_t)z * p.M + gr) * p.N + gc) = v;
     } else {
       float4 u = v;
       if (EPI == EPI_SWIGLU) u = *reinterpret_cast<const float4 *>(sC + r * pitch + OUT_COLS + c);
+      // the tile holds whole heads (its width is a multiple of head_dim), so the partner is parked too
+      if (EPI == EPI_SEG && p.rope_half)
+        u = *reinterpret_cast<const float4 *>(sC + r * pitch + c + rope_partner_offset(p, gc));
       apply_epilogue<T, EPI>(v, u, gr, gc, p);
     }
   }
@@ -728,7 +759,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p) {
     const float4 v = *reinterpret_cast<const float4 *>(p.partial + (size_t)z * p.M * p.N + e);
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
-  apply_epilogue<T, EPI>(acc, acc, r, c, p);
+  float4 partner = acc;
+  if (EPI == EPI_SEG && p.rope_half) {
+    const size_t ep = (size_t)((long)e + rope_partner_offset(p, c));
+    partner = make_float4(0, 0, 0, 0);
+    for (int z = 0; z < p.splits; ++z) {
+      const float4 v = *reinterpret_cast<const float4 *>(p.partial + (size_t)z * p.M * p.N + ep);
+      partner.x += v.x; partner.y += v.y; partner.z += v.z; partner.w += v.w;
+    }
+  }
+  apply_epilogue<T, EPI>(acc, partner, r, c, p);
 }
 
 // ---------------------------------------------------------------------------
@@ -743,6 +783,7 @@ struct GemmPlan {
   int tail_first, tail_splits, tail_k_per_split;   // EPI_SWIGLU tail sharing (tail_splits <= 1: none)
   long grid_ids;                                   // kind 2: workgroups of the main launch
   size_t partial_floats;
+  bool bad;                                        // needs scratch the caller did not give
 };
 
 static int pick_row_blocks(int M) {
@@ -871,8 +912,15 @@ static int problem_n(const GemmArgs &g) {
   return n;
 }
 
-size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K) {
+// The float kernel's 64-column tile does not hold a whole 128-channel head, so it cannot pair
+// channel i with i + head_dim/2 itself: it parks its sums and the reduce launch rotates them.
+static bool needs_raw_partial(int dtype, int epi, int rope_half, int head_dim) {
+  return dtype == 0 && epi == EPI_SEG && rope_half && head_dim > BN32;
+}
+
+size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int rope_half, int head_dim) {
   if (M <= 0) return 0;
+  if (needs_raw_partial(dtype, epi, rope_half, head_dim)) return (size_t)M * N;
   return make_plan(dtype, epi, M, N, K).partial_floats;
 }
 
@@ -890,7 +938,16 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   p.N = problem_n(g);
   p.rope_tab = g.rope_tab; p.row_pos = g.row_pos; p.head_dim = g.head_dim;
   p.out_f32 = g.out_f32; p.resid = g.resid; p.resid_rows = g.resid_rows; p.partial = g.partial;
+  p.rope_half = g.rope_half;
   GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K);
+  if (needs_raw_partial(g.dtype, g.epi, g.rope_half, g.head_dim)) {
+    pl.partial_floats = (size_t)g.M * p.N;
+    pl.bad = !g.partial || g.partial_floats < pl.partial_floats;   // no other way to compute this
+    p.raw_partial = 1;
+    p.splits = 1;
+    p.k_per_split = pl.k_per_split;
+    return pl;
+  }
   if (pl.partial_floats > 0 && (!g.partial || g.partial_floats < pl.partial_floats)) {
     // no scratch: one pass over K
     if (pl.kind == 2) pl.grid_ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
@@ -910,7 +967,7 @@ bool gemm_needs_reduce(const GemmArgs &g) {
   if (g.M == 0) return false;
   GemmParams p;
   const GemmPlan pl = fill_params(g, &p);
-  return pl.splits > 1 || pl.tail_splits > 1;
+  return pl.splits > 1 || pl.tail_splits > 1 || p.raw_partial;
 }
 
 template <int I, int NB, int EPI, int NWV>
@@ -961,6 +1018,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t s) {
   if (g.M == 0) return hipSuccess;
   GemmParams p;
   const GemmPlan pl = fill_params(g, &p);
+  if (pl.bad) return hipErrorInvalidValue;
   if (g.epi == EPI_SEG) launch_typed<EPI_SEG>(pl, p, s);
   else if (g.epi == EPI_SWIGLU) launch_typed<EPI_SWIGLU>(pl, p, s);
   else launch_typed<EPI_F32>(pl, p, s);
@@ -984,7 +1042,8 @@ hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
 #undef CB_TAIL
     return hipGetLastError();
   }
-  if (pl.splits <= 1) return hipSuccess;
+  if (pl.bad) return hipErrorInvalidValue;
+  if (pl.splits <= 1 && !p.raw_partial) return hipSuccess;
   const size_t total4 = (size_t)g.M * p.N / 4;
   const dim3 grid((unsigned)((total4 + 255) / 256));
   if (g.dtype == 0) {

@@ -9,9 +9,10 @@ namespace cb {
 // ---- elementwise.hip -------------------------------------------------------
 // In-place rotation of cached keys of chunks >= 1 by their offsets.
 // rope_tab: float2 [max_tokens][head_dim/2] = (cos, sin)(p * theta_i).
+// rope_half: rotary block i acts on channels (i, i + head_dim/2) of a head instead of (2i, 2i+1).
 hipError_t launch_realign(int dtype, void *const *k_layers_host, int n_layers,
                           const int32_t *chunk_offsets_host, int n_chunks, int kv_dim,
-                          int head_dim, const float2 *rope_tab, hipStream_t s);
+                          int head_dim, int rope_half, const float2 *rope_tab, hipStream_t s);
 hipError_t launch_to_f32(int dtype, const void *x, float *out, size_t n, hipStream_t s);
 // out[r] = rmsnorm(h[r]) * gain, r < n_rows; out has storage type.
 hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int n_rows,
@@ -60,6 +61,7 @@ struct GemmArgs {
   GemmSeg seg[3];          //   (dst/ld_dst of seg[0] receive silu(gate)*up);
                            // EPI_F32: seg[0] only (w, n)
   const float2 *rope_tab;  // EPI_SEG with rope
+  int rope_half;           // rotary pairs (i, i + head_dim/2) instead of (2i, 2i+1); segments are whole heads
   const int32_t *row_pos;  // positions of the logical rows
   int head_dim;
   float *out_f32;          // EPI_F32: [M, n] float output, pitch n
@@ -70,7 +72,7 @@ struct GemmArgs {
 };
 // Floats of split-K scratch a problem of this shape uses (0 when it is not split); N is the
 // total number of output columns (d_ff for EPI_SWIGLU).  For workspace sizing.
-size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K);
+size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int rope_half = 0, int head_dim = 0);
 // Main kernel.  A problem that was split along K (gemm_needs_reduce) leaves raw partial sums
 // in g.partial and must be completed by launch_gemm_reduce on the same stream.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);

@@ -74,6 +74,9 @@ def test_status_strings_and_host_side_rejections(lib):
     with pytest.raises(CacheBlendError) as e:
         P.cb_create(ModelShape(0, 256, 4, 2, 64, 688, 1e-5, 1e4, "f32"), 64)
     assert e.value.status == -1
+    from paper_2405_16444_amd.binding import _ModelDesc
+    desc, handle = _ModelDesc(2, 256, 4, 2, 64, 688, 1e-5, 1e4, 0, 7), ctypes.c_void_p()   # no such rotary order
+    assert lib.cb_create(ctypes.byref(desc), 64, ctypes.byref(handle)) == -1 and not handle.value
     lib.cb_layer_workspace_bytes.restype = ctypes.c_size_t
     assert lib.cb_layer_workspace_bytes(None, 10) == 0
 
