@@ -160,9 +160,10 @@ int cb_fuse_prefill(cb_ctx *ctx, const cb_layer_weights *layers, const void *x,
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /* The same pass with the pre-computed caches still in HOST memory (Sec. 5: pipelining KV
- * loading and recompute).  The copies of all layers are queued on copy_stream at once, in layer
- * order; on `stream`, layer l waits for its own copy only, is re-aligned and fused, so loading
- * layer l+1.. overlaps the recompute of layer l.
+ * loading and recompute).  The copies are queued on copy_stream in layer order, a few layers
+ * ahead of the launches of the layer that needs them; on `stream`, layer l waits for its own copy
+ * only, is re-aligned and fused, so loading layer l+1.. overlaps the recompute of layer l.  Layer 0 recomputes every row and reads none of
+ * its cached K/V, so k_host_layers[0] / v_host_layers[0] are not loaded (they must still be non-NULL).
  *   k_host_layers, v_host_layers : HOST arrays [L] of HOST pointers to T [n_ctx, Hkv, dh], each
  *                   chunk cached at positions 0..; pinned memory if the copies are to overlap
  *   k_cache_layers, v_cache_layers : HOST arrays [L] of device pointers to

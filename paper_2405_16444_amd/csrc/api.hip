@@ -522,8 +522,8 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
   }
   if (cb_prefill_workspace_bytes(c, T) > workspace_bytes) return CB_EWORKSPACE;
   if (k_host) {
-    // the copies of every layer are queued now; the copy stream first waits for whatever the
-    // compute stream still has in flight on the destination buffers
+    // the copy stream first waits for whatever the compute stream still has in flight on the
+    // destination buffers
     while ((int)c->load_events.size() < L + 1) {
       hipEvent_t e = nullptr;
       CB_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -532,13 +532,18 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
     hipStream_t cs = (hipStream_t)copy_stream;
     CB_HIP(hipEventRecord(c->load_events[0], (hipStream_t)stream));
     CB_HIP(hipStreamWaitEvent(cs, c->load_events[0], 0));
-    const size_t bytes = (size_t)C * c->m.n_kv_heads * c->m.head_dim * esize(c);
-    for (int l = 0; l < L; ++l) {
-      CB_HIP(hipMemcpyAsync(k_cache_layers[l], k_host[l], bytes, hipMemcpyHostToDevice, cs));
-      CB_HIP(hipMemcpyAsync(v_cache_layers[l], v_host[l], bytes, hipMemcpyHostToDevice, cs));
-      CB_HIP(hipEventRecord(c->load_events[1 + l], cs));
-    }
   }
+  // Copy of layer l's pre-computed K/V, queued on the copy stream.  Layer 0 recomputes every row
+  // (keep_counts[0] == n_ctx) and never reads its cached K/V, so it has no copy.
+  auto queue_load = [&](int l) -> hipError_t {
+    if (!k_host || l < 1 || l >= L) return hipSuccess;
+    hipStream_t cs = (hipStream_t)copy_stream;
+    const size_t bytes = (size_t)C * c->m.n_kv_heads * c->m.head_dim * esize(c);
+    hipError_t e = hipMemcpyAsync(k_cache_layers[l], k_host[l], bytes, hipMemcpyHostToDevice, cs);
+    if (e == hipSuccess) e = hipMemcpyAsync(v_cache_layers[l], v_host[l], bytes, hipMemcpyHostToDevice, cs);
+    if (e == hipSuccess) e = hipEventRecord(c->load_events[1 + l], cs);
+    return e;
+  };
 
   hipStream_t s = (hipStream_t)stream;
   char *base = (char *)workspace;
@@ -554,15 +559,20 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
     CB_HIP(hipGetLastError());
   }
   int st = CB_OK;
-  if (!k_host) {
-    st = cb_realign_rope(c, k_cache_layers, 0, L, off.data(), n_chunks, stream);
+  if (!k_host && L > 1) {      // layer 0 overwrites all of its rows: nothing of it to re-align
+    st = cb_realign_rope(c, k_cache_layers, 1, L, off.data(), n_chunks, stream);
     if (st != CB_OK) return st;
   }
 
+  // The host runs far ahead of the device, so queueing the copies two layers ahead of the layer
+  // being launched keeps the copy stream busy from the start without holding back the first launch.
+  CB_HIP(queue_load(1));
+  CB_HIP(queue_load(2));
   int n = T;
   for (int l = 0; l < L; ++l) {
     const int k = keep_counts[l];
-    if (k_host) {
+    CB_HIP(queue_load(l + 3));
+    if (k_host && l > 0) {
       CB_HIP(hipStreamWaitEvent(s, c->load_events[1 + l], 0));
       st = cb_realign_rope(c, k_cache_layers, l, l + 1, off.data(), n_chunks, stream);
       if (st != CB_OK) return st;
