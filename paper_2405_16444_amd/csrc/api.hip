@@ -700,9 +700,9 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
     CB_HIP(hipGetLastError());
   }
   std::vector<void *> kptr(L);
-  for (int b = 0; b < B; ++b) {
+  for (int b = 0; b < B && L > 1; ++b) {     // layer 0 overwrites all of its rows: nothing of it to re-align
     for (int l = 0; l < L; ++l) kptr[l] = (char *)k_cache_layers[l] + (size_t)b * cache_stride * kv_row;
-    int st = cb_realign_rope(c, kptr.data(), 0, L, off[b].data(), n_chunks[b], stream);
+    int st = cb_realign_rope(c, kptr.data(), 1, L, off[b].data(), n_chunks[b], stream);
     if (st != CB_OK) return st;
   }
 
