@@ -48,6 +48,8 @@ def parse():
                     help="requests fused per call (cb_fuse_prefill_batched when > 1; distinct inputs per request)")
     ap.add_argument("--no-host-load", action="store_true",
                     help="skip the variant that loads the chunk caches from pinned host memory")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the variant that replays the call from a HIP graph")
     return ap.parse_args()
 
 
@@ -272,6 +274,28 @@ def main():
                     "avg_launch_us": g["ms"] / g["launches"] * 1e3,
                     "flops_per_launch": g["flops"] / g["launches"]}
 
+    # ---- the same call recorded once into a HIP graph and replayed (not part of `value`: a graph
+    # serves requests of one chunk structure and schedule only) ----
+    graph_replay = None
+    if not a.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        restore()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            step()
+        torch.cuda.synchronize()
+        g_ms = []
+        for i in range(2 + min(a.steps, 5)):
+            restore()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            graph.replay()
+            torch.cuda.synchronize()
+            if i >= 2:
+                g_ms.append((time.perf_counter() - t0) * 1e3)
+        graph_replay = {"ttft_ms": float(np.mean(g_ms)), "steps": len(g_ms)}
+        del graph
+
     # ---- first-token head on the prefill's final hidden states (not part of `value`) ----
     head = synth.head_weights(m, w.seed_weights, device=dev)
     logits, token = P.cb_first_token(ctx, bench_out.final_hidden, head["final_norm"], head["lm_head"])
@@ -340,7 +364,7 @@ def main():
                    "schedule": "flat" if a.flat else "gradual", "keep_first": keep[1] if L > 1 else C,
                    "keep_last": keep[-1], "token_layers": token_layers},
         "roofline": roofline, "cpu_baseline": cpu, "kernel_classes": classes, "first_token": first_token,
-        "host_load": host_load,
+        "host_load": host_load, "graph_replay": graph_replay,
     }
     print(json.dumps(res))
 

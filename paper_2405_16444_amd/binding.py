@@ -153,7 +153,8 @@ class Context:
         self.device = torch.device("cuda", torch.cuda.current_device())
 
     def close(self):
-        if getattr(self, "_h", None):
+        # at interpreter shutdown the module globals may already be gone; the process is ending anyway
+        if getattr(self, "_h", None) and _lib is not None:
             _lib.cb_destroy(self._h)
             self._h = None
 
