@@ -136,8 +136,9 @@ int cb_fuse_layer(cb_ctx *ctx, int32_t layer, const cb_layer_weights *weights /*
                   const int32_t *forced_sel, float *h_out, int32_t *pos_out, float *dev_out,
                   void *workspace, size_t workspace_bytes, void *stream);
 
-/* Whole fusing pass (Sec. 4; Sec. 5.1 "fusor"): cb_realign_rope on every layer,
- * then cb_fuse_layer for layers 0 .. L-1, each layer's survivors feeding the next.
+/* Whole fusing pass (Sec. 4; Sec. 5.1 "fusor"): cb_realign_rope on layers 1 .. L-1 (layer 0
+ * keeps, i.e. recomputes, every context row, so its pre-computed K/V is never read), then
+ * cb_fuse_layer for layers 0 .. L-1, each layer's survivors feeding the next.
  *   layers        : HOST array [L] of cb_layer_weights
  *   x             : T [n_ctx + n_suffix, d] layer-0 input, context tokens chunk
  *                   after chunk, then the suffix
