@@ -30,7 +30,7 @@ PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}
 # by what the same counter reads for kernels of known size in the same run (FETCH_SIZE x 1.999,
 # WRITE_SIZE x 1.000); summary under profiles/.  Keyed by (workload, schedule, layers, ratio):
 # any other run reports null.
-PMC_TRAFFIC_BYTES_PER_GEMM_LAUNCH = {("mistral7b", "gradual", 32, 0.15): 236.9e6}
+PMC_TRAFFIC_BYTES_PER_GEMM_LAUNCH = {("mistral7b", "gradual", 32, 0.15): 216.7e6}
 
 
 def parse():

@@ -49,6 +49,9 @@ struct GemmParams {
   // EPI_SWIGLU: workgroup ids >= tail_first share the tiles of the last, partly filled round of
   // workgroups, tail_splits of them per tile, each over tail_k_per_split of K
   int tail_first, tail_splits, tail_k_per_split;
+  // K split dealt to the XCDs (splits = 2, 4 or 8): XCD x computes split x % splits of the n-tiles
+  // congruent to x / splits mod 8 / splits, so each L2 holds only its own K slice of the activations
+  int xcd_split;
 };
 
 // weight row that feeds tile column gc (clamped into range)
@@ -197,6 +200,8 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //   tile order  1-D grid; workgroup id -> (xcd = id % 8, j = id / 8); an XCD walks
 //               its own n-tiles (n % 8 == xcd) in groups of 8 m-tiles (xcd_tile), so the
 //               workgroups that share a weight or activation tile run together on one L2.
+//               With a K split of 2, 4 or 8 the XCDs are dealt one split each (GemmParams::xcd_split),
+//               so an L2 only ever fetches its own K slice of the activations.
 // Requires K % 64 == 0 and k_per_split % 64 == 0.
 // ---------------------------------------------------------------------------
 constexpr int DMA_BK = 64;
@@ -236,12 +241,12 @@ __device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "mem
 // its L2 serves several of them (with all row tiles innermost, a problem with many row tiles
 // would share no activation tile at all).
 constexpr int kGroupM = 8;
-__device__ __forceinline__ void xcd_tile(int j, int xcd, int tiles_m, int nblk, int *nt, int *mt) {
+__device__ __forceinline__ void xcd_tile(int j, int xcd, int tiles_m, int nblk, int *nt, int *mt, int stride = 8) {
   const int per_group = nblk * kGroupM, full = tiles_m / kGroupM;
   int g = j / per_group, r, gm;
   if (g >= full) { g = full; r = j - full * per_group; gm = tiles_m - full * kGroupM; }
   else { r = j - g * per_group; gm = kGroupM; }
-  *nt = xcd + 8 * (r / gm);
+  *nt = xcd + stride * (r / gm);
   *mt = g * kGroupM + r % gm;
 }
 
@@ -335,11 +340,17 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     tail_z = v % p.tail_splits;
     j = (p.tail_first >> 3) + v / p.tail_splits;
   }
-  const int nblk = (tiles_n + 7) >> 3;
-  const int per_z = nblk * tiles_m;
-  const int z = j / per_z, rem = j - z * per_z;
-  int nt, mt;
-  xcd_tile(rem, xcd, tiles_m, nblk, &nt, &mt);
+  int z, nt, mt;
+  if (EPI != EPI_SWIGLU && p.xcd_split) {
+    const int groups = 8 / p.splits;                 // XCDs that share one split
+    z = xcd % p.splits;
+    xcd_tile(j, xcd / p.splits, tiles_m, (tiles_n + groups - 1) / groups, &nt, &mt, groups);
+  } else {
+    const int nblk = (tiles_n + 7) >> 3;
+    const int per_z = nblk * tiles_m;
+    z = j / per_z;
+    xcd_tile(j - z * per_z, xcd, tiles_m, nblk, &nt, &mt);
+  }
   if (nt >= tiles_n) return;
   const int m0 = mt * BM, n0 = nt * OUT_COLS;
   const int kps = tail_z >= 0 ? p.tail_k_per_split : p.k_per_split;
@@ -782,6 +793,7 @@ struct GemmPlan {
   int tiles_m, tiles_n, splits, k_per_split;
   int tail_first, tail_splits, tail_k_per_split;   // EPI_SWIGLU tail sharing (tail_splits <= 1: none)
   long grid_ids;                                   // kind 2: workgroups of the main launch
+  int xcd_split;                                   // kind 2: splits dealt to XCDs (see GemmParams)
   size_t partial_floats;
   bool bad;                                        // needs scratch the caller did not give
 };
@@ -880,6 +892,10 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   if (pl.kind == 2) {
     const long ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
     pl.grid_ids = ids * pl.splits;
+    if (epi != EPI_SWIGLU && (pl.splits == 2 || pl.splits == 4 || pl.splits == 8)) {
+      pl.xcd_split = 1;
+      pl.grid_ids = 8L * ceil_div(pl.tiles_n, 8 / pl.splits) * pl.tiles_m;
+    }
     pl.tail_first = (int)pl.grid_ids;
     if (epi == EPI_SWIGLU) {
       // The last round of 256 workgroups, when less than half full, is shared: ts workgroups per
@@ -951,6 +967,7 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   if (pl.partial_floats > 0 && (!g.partial || g.partial_floats < pl.partial_floats)) {
     // no scratch: one pass over K
     if (pl.kind == 2) pl.grid_ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
+    pl.xcd_split = 0;
     pl.splits = 1;
     pl.k_per_split = ceil_div(g.K, pl.bk) * pl.bk;
     pl.tail_splits = 1;
@@ -960,6 +977,7 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   p.splits = pl.splits;
   p.k_per_split = pl.k_per_split;
   p.tail_first = pl.tail_first; p.tail_splits = pl.tail_splits; p.tail_k_per_split = pl.tail_k_per_split;
+  p.xcd_split = pl.xcd_split;
   return pl;
 }
 
