@@ -18,6 +18,9 @@
  *   - Weight matrices are row-major [out_features, in_features] (y = x W^T).
  *   - A layer's K cache and V cache are separate arrays [n_tokens, n_kv_heads,
  *     head_dim] of T, token-major; row p holds the token at global position p.
+ *   - Alignment: device pointers to tensors (weights, x, caches, h_in / h_out, final_hidden,
+ *     logits) must be multiples of 16 bytes, index and deviation arrays of 4 bytes, workspaces of
+ *     256 bytes; anything else is refused with CB_EINVAL before any launch.
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and return without synchronising the device.  Results are
  *     valid once the caller has synchronised the stream.

@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -139,12 +140,23 @@ __global__ void iota_kernel(int32_t *p, int n, int base) {
     if (e_ != hipSuccess) return CB_EHIP; \
   } while (0)
 
+// The kernels move tensors in 16-byte vectors and index arrays in 4-byte words: a pointer that is
+// not aligned accordingly would fault on the device, so it is refused on the host.  NULL passes
+// (whether NULL is allowed is checked separately).
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+bool weights_aligned(const cb_layer_weights *w) {
+  return aligned(w->attn_norm, 16) && aligned(w->wq, 16) && aligned(w->wk, 16) && aligned(w->wv, 16) &&
+         aligned(w->wo, 16) && aligned(w->mlp_norm, 16) && aligned(w->w_gate, 16) && aligned(w->w_up, 16) &&
+         aligned(w->w_down, 16);
+}
+
 int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int n_rows, int n_suffix,
                      int n_tokens_total, int k_keep) {
   if (!c || !w) return CB_ENULL;
   if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up ||
       !w->w_down)
     return CB_ENULL;
+  if (!weights_aligned(w)) return CB_EINVAL;
   if (layer < 0 || layer >= c->m.n_layers) return CB_EINVAL;
   if (n_rows < 0 || n_suffix < 0 || n_suffix > n_rows) return CB_EINVAL;
   if (k_keep < 0 || k_keep > n_rows - n_suffix) return CB_EINVAL;
@@ -454,8 +466,10 @@ int cb_realign_rope(cb_ctx *c, void *const *k_cache_layers, int32_t layer_begin,
   for (int i = 0; i < n_chunks; ++i)
     if (chunk_offsets[i + 1] <= chunk_offsets[i]) return CB_EINVAL;
   if (chunk_offsets[n_chunks] > c->max_tokens) return CB_EINVAL;
-  for (int l = layer_begin; l < layer_end; ++l)
+  for (int l = layer_begin; l < layer_end; ++l) {
     if (!k_cache_layers[l]) return CB_ENULL;
+    if (!aligned(k_cache_layers[l], 16)) return CB_EINVAL;
+  }
   if (layer_begin == layer_end || n_chunks == 1) return CB_OK;
   hipStream_t s = (hipStream_t)stream;
   const int kv_dim = c->m.n_kv_heads * c->m.head_dim;
@@ -476,6 +490,10 @@ int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const flo
   if (st != CB_OK) return st;
   if (!h_in || !row_pos || !k_cache || !v_cache || !h_out || !pos_out || !workspace) return CB_ENULL;
   if (h_out == h_in || pos_out == row_pos) return CB_EINVAL;
+  if (!aligned(h_in, 16) || !aligned(h_out, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) ||
+      !aligned(row_pos, 4) || !aligned(pos_out, 4) || !aligned(forced_sel, 4) || !aligned(dev_out, 4) ||
+      !aligned(workspace, 256))
+    return CB_EINVAL;
   if (n_rows == 0) return CB_OK;
   LayerWs ws = carve_layer(c, (char *)workspace, n_rows);
   if (ws.bytes > workspace_bytes) return CB_EWORKSPACE;
@@ -514,9 +532,14 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
   if (keep_counts[0] != C) return CB_EINVAL;
   for (int l = 1; l < L; ++l)
     if (keep_counts[l] < 0 || keep_counts[l] > keep_counts[l - 1]) return CB_EINVAL;
+  if (!aligned(x, 16) || !aligned(final_hidden, 16) || !aligned(workspace, 256)) return CB_EINVAL;
   for (int l = 0; l < L; ++l) {
     if (!k_cache_layers[l] || !v_cache_layers[l]) return CB_ENULL;
     if (k_host && (!k_host[l] || !v_host[l])) return CB_ENULL;
+    if (!aligned(k_cache_layers[l], 16) || !aligned(v_cache_layers[l], 16)) return CB_EINVAL;
+    if ((forced_sel && !aligned(forced_sel[l], 4)) || (sel_dump && !aligned(sel_dump[l], 4)) ||
+        (dev_dump && !aligned(dev_dump[l], 4)))
+      return CB_EINVAL;
     int st = check_layer_args(c, l, &layers[l], T, n_suffix, T, 0);
     if (st != CB_OK) return st;
   }
@@ -670,13 +693,20 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
   }
   if (total > (1 << 24) || (long)B * cache_stride > (1L << 30)) return CB_EINVAL;
   if (total_suffix > 0 && !final_hidden) return CB_ENULL;
+  if (!aligned(x, 16) || !aligned(final_hidden, 16) || !aligned(workspace, 256)) return CB_EINVAL;
   for (int l = 0; l < L; ++l) {
     if (!k_cache_layers[l] || !v_cache_layers[l]) return CB_ENULL;
     const cb_layer_weights *w = &layers[l];
     if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up ||
         !w->w_down)
       return CB_ENULL;
+    if (!weights_aligned(w) || !aligned(k_cache_layers[l], 16) || !aligned(v_cache_layers[l], 16) ||
+        (dev_dump && !aligned(dev_dump[l], 4)))
+      return CB_EINVAL;
   }
+  if (sel_dump)
+    for (size_t i = 0; i < (size_t)B * L; ++i)
+      if (!aligned(sel_dump[i], 4)) return CB_EINVAL;
   const int N = (int)total;
   if (cb_batched_workspace_bytes(c, N) > workspace_bytes) return CB_EWORKSPACE;
 
@@ -746,6 +776,9 @@ int cb_first_token(cb_ctx *c, const float *final_hidden, int32_t n_suffix, const
                    const void *lm_head, int32_t vocab, float *logits, int32_t *token, void *stream) {
   if (!c || !final_hidden || !final_norm || !lm_head || !logits || !token) return CB_ENULL;
   if (n_suffix < 1 || vocab < 1) return CB_EINVAL;
+  if (!aligned(final_hidden, 16) || !aligned(final_norm, 16) || !aligned(lm_head, 16) || !aligned(logits, 16) ||
+      !aligned(token, 4))
+    return CB_EINVAL;
   const int d = c->m.d_model;
   if (d % 8 != 0 || d > 16384) return CB_EUNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;

@@ -366,6 +366,21 @@ def test_error_codes_leave_buffers_untouched(P):
     assert e.value.status == -3
     with pytest.raises(CacheBlendError):
         P.cb_realign_rope(ctx, [kg, kg], 0, 2, [0, 50, 40])
+    # pointers the 16-byte vector accesses could not take: refused on the host, nothing launched
+    big = torch.zeros(kg.numel() + 8, dtype=kg.dtype, device="cuda")
+    k_odd = big[1:1 + kg.numel()].view(kg.shape)                      # 4 bytes off
+    h_odd = torch.zeros(h.numel() + 4, device="cuda")[1:1 + h.numel()].view(h.shape)
+    for args in [(h.cuda(), k_odd, vg), (h_odd, kg, vg), (h.cuda(), kg, k_odd)]:
+        with pytest.raises(CacheBlendError) as e:
+            P.cb_fuse_layer(ctx, 0, dlw, args[0], pos.cuda(), 4, args[1], args[2], 10)
+        assert e.value.status == -1
+    with pytest.raises(CacheBlendError) as e:
+        P.cb_realign_rope(ctx, [kg, k_odd], 0, 2, [0, 40, 100])
+    assert e.value.status == -1
+    ws = torch.empty(P.cb_layer_workspace_bytes(ctx, 40) + 64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(CacheBlendError) as e:
+        P.cb_fuse_layer(ctx, 0, dlw, h.cuda(), pos.cuda(), 4, kg, vg, 10, workspace=ws[16:])
+    assert e.value.status == -1
     torch.cuda.synchronize()
-    assert torch.equal(kg.cpu(), kc) and torch.equal(vg.cpu(), vc)
+    assert torch.equal(kg.cpu(), kc) and torch.equal(vg.cpu(), vc) and not bool(big.any())
     P.cb_destroy(ctx)
