@@ -251,6 +251,8 @@ def kv_deviation(k_new, v_new, k_old, v_old):
     dk = np.asarray(k_new, F64) - np.asarray(k_old, F64)
     dv = np.asarray(v_new, F64) - np.asarray(v_old, F64)
     n = dk.shape[0]
+    if n == 0:                      # no candidate left (numpy cannot infer the row length of an empty array)
+        return np.zeros(0, F64)
     return (dk * dk).reshape(n, -1).sum(axis=1) + (dv * dv).reshape(n, -1).sum(axis=1)
 
 

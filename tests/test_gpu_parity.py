@@ -305,6 +305,22 @@ def test_ratio_one_is_full_prefill_and_ratio_zero_is_plain_reuse(P, name):
         assert max_abs_rel(to_np(kg0[l].cpu()), ref0.K[l]) < tol
 
 
+@pytest.mark.parametrize("name,lens,n_suffix,keep", [
+    ("bf16", (100, 140, 60), 0, (300, 45, 0)),      # no query rows; the last layer has no row at all
+    ("f32", (64, 64), 0, (128, 0, 0)),              # nothing but layer 0
+    ("bf16", (1,), 1, (1, 1, 0)),                   # one context token, one query token
+    ("f32", (1, 1, 1), 0, (3, 2, 1)),               # three one-token chunks
+    ("bf16", (257,), 3, (257, 100, 20)),            # a single chunk: a prefix, nothing to re-align
+])
+def test_prefill_degenerate_requests(P, name, lens, n_suffix, keep):
+    model = replace(MODELS[name], n_layers=3)
+    announce("degenerate request", name, lens, n_suffix, keep)
+    w, layers, x, npl, xn, kpre, vpre = e2e_case(model, lens, n_suffix, seed=300 + len(lens))
+    out, kg, vg = run_prefill(P, w, layers, x, kpre, vpre, list(keep))
+    assert out.final_hidden.shape == (n_suffix, model.d_model)
+    check_prefill_against_oracle(w, npl, xn, kpre, vpre, list(keep), out, kg, vg, TOL[model.dtype])
+
+
 def test_layer_calls_equal_one_prefill_call_bitwise(P):
     model = replace(BF16_M, n_layers=3)
     announce("layer calls == prefill call")

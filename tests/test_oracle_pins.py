@@ -141,6 +141,19 @@ def test_half_split_model_equals_adjacent_model_with_renumbered_projections():
     assert np.abs(wrong.final_hidden - a.final_hidden).max() > 1e-3
 
 
+def test_request_without_query_rows_and_without_survivors_is_plain_reuse():
+    """No suffix and nothing kept after layer 0: later layers see no row at all, their caches are
+    the re-aligned pre-computed ones, and there is no final hidden state."""
+    layers, npl, x, xn = make(SMALL_W)
+    C = SMALL_W.n_ctx
+    kpre, vpre = O.chunk_prefill(xn[:C], SMALL_W.chunk_lens, npl, SMALL)
+    out = O.fuse_prefill(xn[:C], npl, SMALL, SMALL_W.chunk_lens, 0, kpre, vpre, [C, 0, 0])
+    assert out.final_hidden.shape == (0, SMALL.d_model) and out.rows == [C, 0, 0]
+    for l in (1, 2):
+        assert np.array_equal(out.K[l], O.realign_keys(kpre[l], SMALL_W.chunk_lens, SMALL))
+        assert np.array_equal(out.V[l], vpre[l]) and len(out.sel[l]) == 0
+
+
 # ------------------------------------------------------- block pieces -------
 def test_rmsnorm_silu_bf16_against_torch():
     rng = np.random.default_rng(3)
