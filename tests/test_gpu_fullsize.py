@@ -72,6 +72,7 @@ def run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, want_dev):
     ("yi34b", 3136, 525, 64, 400),            # 7 query heads per kv head, d = 7168
     ("llama70b", 4064, 300, 64, 200),         # 8 query heads per kv head, d = 8192, d_ff = 28672
     ("long32k", 32896, 700, 128, 500),        # 32 K-token cache: attention KV split + long positions
+    ("long32k", 131200, 400, 128, 200),       # 128 K-token cache: 1025 key tiles, positions beyond 2^17
 ])
 def test_selective_layer_at_real_width(P, name, n_tokens, n_rows, n_suffix, k_keep):
     w = WORKLOADS[name]
