@@ -14,7 +14,7 @@ import torch  # imported before the library so both share one HIP runtime
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcacheblend.so")
 
 CB_F32, CB_BF16 = 0, 1
-PROF_CLASSES = ("gemm", "attention", "realign", "deviation", "topk", "norm", "other", "splitk_reduce",
+PROF_CLASSES = ("gemm", "attention", "realign", "deviation", "topk", "norm", "other", "finish",
                 "first_token")
 
 

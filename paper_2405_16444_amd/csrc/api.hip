@@ -35,6 +35,7 @@ struct cb_ctx {
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> free_events;
   std::vector<hipEvent_t> load_events;   // pipelined loading: [0] = entry fence, [1 + l] = layer l landed
+  mutable std::vector<size_t> partial_memo;   // [rows] -> scratch floats layer calls with <= rows rows can use
 };
 
 namespace {
@@ -74,33 +75,42 @@ struct ProfScope {
 };
 
 struct LayerWs {
-  void *xn, *kvnew, *qbuf, *obuf, *act;
+  void *xn, *xn2, *kvnew, *qbuf, *obuf, *act;
   float *hmid, *partial, *dev;
   int32_t *sel_rows;
   size_t partial_floats;
   size_t bytes;
 };
 
+// bf16 models feed the Q/K/V projections a (high, low) pair per normalised activation, the low
+// parts d_model elements after the high parts of the same row
+int xn_lo_off(const cb_ctx *c) { return c->m.dtype == CB_BF16 ? c->m.d_model : 0; }
+int xn_pitch(const cb_ctx *c) { return c->m.d_model + xn_lo_off(c); }
+
+// Floats of scratch (parked projection sums, attention key-range pieces) that layer calls with up
+// to max_rows rows can use: the maximum over EVERY row count, because neither the K split of a
+// projection nor the number of key-range pieces is monotone in the row count.  Memoised per ctx.
 size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
   const cb_model_desc &m = c->m;
   const int d = m.d_model, q_dim = m.n_q_heads * m.head_dim, kv_dim = m.n_kv_heads * m.head_dim;
-  size_t need = 0;
-  // the split decision depends on M through the tile count only; tiles are multiples of 32 rows
-  for (int M = 32;; M += 32) {
-    const int mm = std::min(M, max_rows);
-    const int rh = m.rope_layout == CB_ROPE_HALF;
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, 2 * kv_dim, d, rh, m.head_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim, d, rh, m.head_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, mm, q_dim + 2 * kv_dim, d, rh, m.head_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, q_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, mm, d, m.d_ff));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, mm, m.d_ff, d));
+  const int rh = m.rope_layout == CB_ROPE_HALF, hl = xn_lo_off(c) > 0;
+  std::vector<size_t> &memo = c->partial_memo;
+  if (memo.empty()) memo.push_back(0);
+  while ((int)memo.size() <= max_rows) {
+    const int M = (int)memo.size();
+    size_t need = memo.back();
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 1, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim + 2 * kv_dim, d, hl, 1, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim, d, hl, 0, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim + 2 * kv_dim, d, hl, 0, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, q_dim, 0, 0, 0, 0));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, m.d_ff, 0, 0, 0, 0));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, M, m.d_ff, d, 0, 0, 0, 0));
     // the attention KV split borrows the same scratch (the two are never live together)
-    need = std::max(need, attention_partial_floats(m.dtype, mm, m.n_q_heads, m.n_kv_heads, m.head_dim,
-                                                   c->max_tokens));
-    if (mm == max_rows) break;
+    need = std::max(need, attention_partial_floats_bound(m.dtype, M, m.n_q_heads, m.n_kv_heads, m.head_dim));
+    memo.push_back(need);
   }
-  return need;
+  return memo[max_rows];
 }
 
 // carve the per-layer workspace out of [base, base + avail); base may be NULL to size only
@@ -115,7 +125,8 @@ LayerWs carve_layer(const cb_ctx *c, char *base, int R) {
     off += align_up(bytes, 256);
     return (void *)p;
   };
-  w.xn = take((size_t)R * m.d_model * es);
+  w.xn = take((size_t)R * xn_pitch(c) * es);
+  w.xn2 = take((size_t)R * m.d_model * es);
   w.kvnew = take((size_t)R * 2 * kv_dim * es);
   w.qbuf = take((size_t)R * q_dim * es);
   w.obuf = take((size_t)R * q_dim * es);
@@ -168,19 +179,42 @@ int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int 
 // k context rows are kept, its caches hold T rows.
 struct Seg { int n, S, k, T; };
 
+// runs a projection: the main launch and, when its sums were parked, the finish launch
+int run_gemm(cb_ctx *c, hipStream_t s, const GemmArgs &g, int finish_class, double flops, double bytes,
+             double finish_bytes) {
+  {
+    ProfScope ps(c, s, CB_PROF_GEMM, flops, bytes);
+    CB_HIP(launch_gemm(g, s));
+  }
+  if (gemm_needs_finish(g)) {
+    ProfScope ps(c, s, finish_class, 0, finish_bytes);
+    CB_HIP(launch_gemm_finish(g, s));
+  }
+  return CB_OK;
+}
+#define CB_TRY(expr)            \
+  do {                          \
+    const int st_ = (expr);     \
+    if (st_ != CB_OK) return st_; \
+  } while (0)
+
 // The layer body; arguments already validated.  Rows of several requests may be stacked
 // (request-major): the projections then run on all of them at once, selection and attention per
 // request.  cache_row (NULL: row_pos) gives each row's row in the cache arrays, which hold the
 // requests' slabs cache_stride rows apart; cache_row_out receives it for the kept rows.
+// xn_ready: ws.xn already holds the normalised input rows (left there by the previous layer's
+// call through next_gain).  next_gain (NULL: none): gain of the RMSNorm that will read h_out;
+// the normalised rows are then left in ws.xn by the launch that finishes h_out.
 int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, const int32_t *row_pos,
                     const int32_t *cache_row, const Seg *segs, int n_segs, size_t cache_stride, void *kc,
                     void *vc, const int32_t *forced, float *h_out, int32_t *pos_out, int32_t *cache_row_out,
-                    float *dev_out, const LayerWs &ws, hipStream_t s) {
+                    float *dev_out, const LayerWs &ws, hipStream_t s, bool xn_ready, const void *next_gain) {
   const cb_model_desc &m = c->m;
   const int dt = m.dtype;
   const size_t es = esize(c);
   const int d = m.d_model, q_dim = m.n_q_heads * m.head_dim, kv_dim = m.n_kv_heads * m.head_dim;
   const int F = m.d_ff;
+  const int lo_off = xn_lo_off(c), xld = xn_pitch(c);
   int n = 0, rows = 0;
   bool check = forced != nullptr;
   for (int b = 0; b < n_segs; ++b) {
@@ -191,81 +225,68 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   if (n == 0) return CB_OK;
   const int32_t *crow = cache_row ? cache_row : row_pos;
 
-  {
-    ProfScope ps(c, s, CB_PROF_NORM, 0, (double)n * d * (4 + es));
-    CB_HIP(launch_rmsnorm(dt, h_in, w->attn_norm, ws.xn, n, d, m.rms_eps, s));
+  if (!xn_ready) {
+    ProfScope ps(c, s, CB_PROF_NORM, 0, (double)n * d * (4 + es * (lo_off ? 2 : 1)));
+    CB_HIP(launch_rmsnorm(dt, h_in, w->attn_norm, ws.xn, xld, lo_off, n, d, m.rms_eps, s));
   }
   GemmArgs g = {};
   g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim; g.rope_half = m.rope_layout == CB_ROPE_HALF;
   g.partial = ws.partial; g.partial_floats = ws.partial_floats;
+  g.a = ws.xn; g.lda = xld; g.a_lo_off = lo_off; g.K = d; g.epi = EPI_SEG;
   const int32_t *sel_rows = nullptr;
   bool q_all = false;
   if (check) {
-    // K/V of every row that reached this layer (Sec. 6: the KV computed anew on this layer)
+    // K/V of every row that reached this layer (Sec. 6: the KV computed anew on this layer), and in
+    // the launch that finishes them the deviation of every candidate from its cached K/V.
     // When nearly every candidate survives (gradual filtering), Q is projected for all candidates
     // in the same launch and attention picks the kept rows through sel_rows; otherwise Q is
     // projected after the selection, for the kept rows only.
     q_all = (long)n * 4 <= (long)rows * 5;
-    g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = q_all ? 3 : 2;
-    g.seg[0] = {w->wk, kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1};
-    g.seg[1] = {w->wv, kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0};
-    g.seg[2] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
+    g.a_rows = nullptr; g.M = n; g.n_seg = q_all ? 3 : 2;
+    g.seg[0] = {w->wk, kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1, kc};
+    g.seg[1] = {w->wv, kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0, vc};
+    g.seg[2] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
     g.row_pos = row_pos;
-    const int n_out = 2 * kv_dim + (q_all ? q_dim : 0);
-    {
-      // flops counted as the method needs them: Q only for the rows that are kept
-      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * 2 * kv_dim + (q_all ? 2.0 * rows * d * q_dim : 0.0),
-                   ((double)n_out * d + (double)n * d + (double)n * n_out) * es);
-      CB_HIP(launch_gemm(g, s));
-    }
-    if (gemm_needs_reduce(g)) {
-      ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-      CB_HIP(launch_gemm_reduce(g, s));
-    }
     float *dev = dev_out ? dev_out : ws.dev;
     // one request: its candidates are the leading rows; several: every row gets a value (a
     // suffix row's is never looked at)
     const int n_dev = n_segs == 1 ? n - segs[0].S : n;
+    g.dev_out = dev; g.n_dev = n_dev; g.dev_row = crow;
+    const int n_out = 2 * kv_dim + (q_all ? q_dim : 0);
+    // flops counted as the method needs them: Q only for the rows that are kept
+    CB_TRY(run_gemm(c, s, g, CB_PROF_DEV, 2.0 * n * d * 2 * kv_dim + (q_all ? 2.0 * rows * d * q_dim : 0.0),
+                    ((double)n_out * d + (double)n * d + (double)n * n_out) * es,
+                    (double)n_dev * (4.0 * kv_dim * es + 4)));
+    g.dev_out = nullptr;
     {
-      ProfScope ps(c, s, CB_PROF_DEV, 4.0 * n_dev * 2 * kv_dim, (double)n_dev * (4.0 * kv_dim * es + 4));
-      CB_HIP(launch_deviation(dt, ws.kvnew, crow, n_dev, kc, vc, kv_dim, dev, s));
-    }
-    {
-      ProfScope ps(c, s, CB_PROF_TOPK, 0, (double)n_dev * 4 + (double)rows * 8);
+      ProfScope ps(c, s, CB_PROF_TOPK, 0, (double)n_dev * 4 + (double)rows * (8 + 4.0 * kv_dim * es));
       if (forced) {
         CB_HIP(launch_forced_map(forced, segs[0].k, row_pos, n - segs[0].S, segs[0].S, ws.sel_rows, pos_out, s));
+        if (cache_row_out && rows > 0) CB_HIP(launch_gather_i32(crow, ws.sel_rows, rows, cache_row_out, s));
+        // only the kept tokens' KV is updated (Sec. 6)
+        CB_HIP(launch_scatter_kv(dt, ws.kvnew, ws.sel_rows, cache_row_out ? cache_row_out : pos_out, rows, kc, vc,
+                                 kv_dim, s));
       } else {
+        // selection and the update of the kept tokens' KV (Sec. 6) in one launch per request
         int in_off = 0, out_off = 0;
         for (int b = 0; b < n_segs; ++b) {
-          CB_HIP(launch_topk(dev + in_off, segs[b].n - segs[b].S, segs[b].k, segs[b].S, row_pos + in_off,
-                             ws.sel_rows + out_off, pos_out + out_off, in_off, s));
+          CB_HIP(launch_topk_scatter(dev + in_off, segs[b].n - segs[b].S, segs[b].k, segs[b].S, row_pos + in_off,
+                                     cache_row ? cache_row + in_off : nullptr, ws.sel_rows + out_off,
+                                     pos_out + out_off, cache_row_out ? cache_row_out + out_off : nullptr, in_off,
+                                     ws.kvnew, kc, vc, (int)(kv_dim * es), s));
           in_off += segs[b].n;
           out_off += segs[b].k + segs[b].S;
         }
       }
-      if (cache_row_out && rows > 0) CB_HIP(launch_gather_i32(crow, ws.sel_rows, rows, cache_row_out, s));
     }
     if (rows == 0) return CB_OK;
     sel_rows = ws.sel_rows;
-    {
-      // only the kept tokens' KV is updated (Sec. 6)
-      ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)rows * 4 * kv_dim * es);
-      CB_HIP(launch_scatter_kv(dt, ws.kvnew, sel_rows, cache_row_out ? cache_row_out : pos_out, rows, kc, vc,
-                               kv_dim, s));
-    }
     if (!q_all) {
       g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
-      g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
+      g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
       g.row_pos = pos_out;
-      {
-        ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * q_dim,
-                     ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es);
-        CB_HIP(launch_gemm(g, s));
-      }
-      if (gemm_needs_reduce(g)) {
-        ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-        CB_HIP(launch_gemm_reduce(g, s));
-      }
+      CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * rows * d * q_dim,
+                      ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es, 0));
     }
   } else {
     // every row is kept: one fused Q|K|V projection, K and V written straight into the cache
@@ -275,20 +296,13 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       if (cache_row_out)
         CB_HIP(hipMemcpyAsync(cache_row_out, crow, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
     }
-    g.a = ws.xn; g.lda = d; g.a_rows = nullptr; g.M = n; g.K = d; g.epi = EPI_SEG; g.n_seg = 3;
-    g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1};
-    g.seg[1] = {w->wk, kv_dim, kc, kv_dim, crow, 1};
-    g.seg[2] = {w->wv, kv_dim, vc, kv_dim, crow, 0};
+    g.a_rows = nullptr; g.M = n; g.n_seg = 3;
+    g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
+    g.seg[1] = {w->wk, kv_dim, kc, kv_dim, crow, 1, nullptr};
+    g.seg[2] = {w->wv, kv_dim, vc, kv_dim, crow, 0, nullptr};
     g.row_pos = row_pos;
-    {
-      ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * n * d * (q_dim + 2 * kv_dim),
-                   ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es);
-      CB_HIP(launch_gemm(g, s));
-    }
-    if (gemm_needs_reduce(g)) {
-      ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-      CB_HIP(launch_gemm_reduce(g, s));
-    }
+    CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * n * d * (q_dim + 2 * kv_dim),
+                    ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es, 0));
   }
   {
     // attention is per request: its rows against its own cache slab
@@ -305,50 +319,28 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       out_off += rows_b;
     }
   }
-  // h = H + o Wo^T
+  // hmid = H + o Wo^T, and its RMSNorm (the MLP's input) from the launch that finishes it
   GemmArgs f = {};
   f.dtype = dt; f.a = ws.obuf; f.lda = q_dim; f.M = rows; f.K = q_dim; f.epi = EPI_F32; f.n_seg = 1;
   f.seg[0].w = w->wo; f.seg[0].n = d;
   f.out_f32 = ws.hmid; f.resid = h_in; f.resid_rows = sel_rows;
+  f.norm_gain = w->mlp_norm; f.norm_out = ws.xn2; f.norm_ld = d; f.norm_lo_off = 0; f.norm_eps = m.rms_eps;
   f.partial = ws.partial; f.partial_floats = ws.partial_floats;
-  {
-    ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * q_dim * d,
-                 ((double)q_dim * d + (double)rows * q_dim) * es + (double)rows * d * 8);
-    CB_HIP(launch_gemm(f, s));
-  }
-  if (gemm_needs_reduce(f)) {
-    ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-    CB_HIP(launch_gemm_reduce(f, s));
-  }
-  {
-    ProfScope ps(c, s, CB_PROF_NORM, 0, (double)rows * d * (4 + es));
-    CB_HIP(launch_rmsnorm(dt, ws.hmid, w->mlp_norm, ws.xn, rows, d, m.rms_eps, s));
-  }
+  CB_TRY(run_gemm(c, s, f, CB_PROF_REDUCE, 2.0 * rows * q_dim * d, ((double)q_dim * d + (double)rows * q_dim) * es,
+                  (double)rows * d * (12 + es)));
   GemmArgs u = {};
-  u.dtype = dt; u.a = ws.xn; u.lda = d; u.M = rows; u.K = d; u.epi = EPI_SWIGLU; u.n_seg = 2;
-  u.seg[0] = {w->w_gate, F, ws.act, F, nullptr, 0};
-  u.seg[1] = {w->w_up, F, nullptr, 0, nullptr, 0};
+  u.dtype = dt; u.a = ws.xn2; u.lda = d; u.M = rows; u.K = d; u.epi = EPI_SWIGLU; u.n_seg = 2;
+  u.seg[0] = {w->w_gate, F, ws.act, F, nullptr, 0, nullptr};
+  u.seg[1] = {w->w_up, F, nullptr, 0, nullptr, 0, nullptr};
   u.partial = ws.partial; u.partial_floats = ws.partial_floats;
-  {
-    ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * d * 2 * F,
-                 ((double)2 * F * d + (double)rows * d + (double)rows * F) * es);
-    CB_HIP(launch_gemm(u, s));
-  }
-  if (gemm_needs_reduce(u)) {
-    ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-    CB_HIP(launch_gemm_reduce(u, s));
-  }
+  CB_TRY(run_gemm(c, s, u, CB_PROF_REDUCE, 2.0 * rows * d * 2 * F,
+                  ((double)2 * F * d + (double)rows * d + (double)rows * F) * es, 0));
+  // h_out = hmid + act Wd^T; the next layer's normalised input comes from the same finish launch
   f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = w->w_down;
   f.out_f32 = h_out; f.resid = ws.hmid; f.resid_rows = nullptr;
-  {
-    ProfScope ps(c, s, CB_PROF_GEMM, 2.0 * rows * F * d,
-                 ((double)F * d + (double)rows * F) * es + (double)rows * d * 8);
-    CB_HIP(launch_gemm(f, s));
-  }
-  if (gemm_needs_reduce(f)) {
-    ProfScope ps(c, s, CB_PROF_REDUCE, 0, 0);
-    CB_HIP(launch_gemm_reduce(f, s));
-  }
+  f.norm_gain = next_gain; f.norm_out = ws.xn; f.norm_ld = xld; f.norm_lo_off = lo_off;
+  CB_TRY(run_gemm(c, s, f, CB_PROF_REDUCE, 2.0 * rows * F * d, ((double)F * d + (double)rows * F) * es,
+                  (double)rows * d * (12 + (next_gain ? es * (lo_off ? 2 : 1) : 0))));
   return CB_OK;
 }
 
@@ -499,7 +491,7 @@ int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const flo
   if (ws.bytes > workspace_bytes) return CB_EWORKSPACE;
   const Seg seg = {n_rows, n_suffix, k_keep, n_tokens_total};
   return fuse_layer_impl(c, w, h_in, row_pos, nullptr, &seg, 1, 0, k_cache, v_cache, forced_sel, h_out, pos_out,
-                         nullptr, dev_out, ws, (hipStream_t)stream);
+                         nullptr, dev_out, ws, (hipStream_t)stream, false, nullptr);
 }
 
 namespace {
@@ -603,8 +595,10 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
     const int32_t *forced = forced_sel ? forced_sel[l] : nullptr;
     float *dev_out = dev_dump ? dev_dump[l] : nullptr;
     const Seg seg = {n, n_suffix, k, T};
+    // the launch that finishes a layer's output also normalises it for the next layer
     st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, nullptr, &seg, 1, 0, k_cache_layers[l], v_cache_layers[l],
-                         forced, h_nxt, p_nxt, nullptr, dev_out, ws, s);
+                         forced, h_nxt, p_nxt, nullptr, dev_out, ws, s, l > 0,
+                         l + 1 < L ? layers[l + 1].attn_norm : nullptr);
     if (st != CB_OK) return st;
     if (sel_dump && sel_dump[l] && k > 0)
       CB_HIP(hipMemcpyAsync(sel_dump[l], p_nxt, (size_t)k * 4, hipMemcpyDeviceToDevice, s));
@@ -742,7 +736,8 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
     for (int b = 0; b < B; ++b) segs[b].k = keep_counts[(size_t)b * L + l];
     int st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, r_cur, segs.data(), B, (size_t)cache_stride,
                              k_cache_layers[l], v_cache_layers[l], nullptr, h_nxt, p_nxt, r_nxt,
-                             dev_dump ? dev_dump[l] : nullptr, ws, s);
+                             dev_dump ? dev_dump[l] : nullptr, ws, s, l > 0,
+                             l + 1 < L ? layers[l + 1].attn_norm : nullptr);
     if (st != CB_OK) return st;
     int o = 0;
     for (int b = 0; b < B; ++b) {

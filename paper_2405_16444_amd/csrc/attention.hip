@@ -1,7 +1,7 @@
-// Sparse-query causal attention of the recomputed rows over the whole fused KV
-// cache (paper Sec. 4.2: "the attention matrix includes attention between selected
-// tokens and all other tokens"); with every row selected it is plain causal
-// attention (Sec. 2).  A query at global position p sees cache rows 0..p.
+// Sparse-query causal attention (paper Sec. 4.2): the recomputed rows are the queries,
+// the keys and values are ALL rows of the fused cache, recomputed or reused; with every
+// row selected it is plain causal attention (Sec. 2).  A query at global position p
+// sees cache rows 0..p.
 //
 // bf16 kernel (MFMA 32x32x16).  One workgroup = one kv head x a block of
 // "flattened queries" m = row * g + head_in_group, so the g query heads that share
@@ -21,6 +21,7 @@
 #include "common.h"
 #include "kernels.h"
 #include <algorithm>
+#include <mutex>
 
 namespace cb {
 
@@ -41,7 +42,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
                                                         int n_q_heads, int n_kv_heads, float scale_log2e,
                                                         int split_tiles, float *__restrict__ part_o,
                                                         float *__restrict__ part_ml,
-                                                        const int32_t *__restrict__ q_rows) {
+                                                        const int32_t *__restrict__ q_rows,
+                                                        int32_t *__restrict__ wg_tiles) {
   // K and V tiles sit row-major in LDS ([key][channel], no padding) and are filled by direct
   // global->LDS loads: one wavefront-wide 16-byte load writes 1 KB = RPI whole rows.  Instead of
   // padding, the 16-byte chunk c of row r is stored in slot c ^ f(r), which makes both the
@@ -66,10 +68,22 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
   const int m_wg = (int)(gridDim.y - 1 - blockIdx.y) * WGQ;
   const int kv_dim = n_kv_heads * DH;
 
-  // causal bound of the workgroup = position of its last valid row
-  const int last_m = min(m_wg + WGQ, n_flat) - 1;
-  const int kv_len = q_pos[last_m / g] + 1;
+  // causal bound of the workgroup = largest position among its rows (they need not be sorted)
+  __shared__ int s_max_pos;
+  if (tid == 0) s_max_pos = -1;
+  __syncthreads();
+  {
+    const int last_m = min(m_wg + WGQ, n_flat) - 1;
+    int mp = -1;
+    for (int r = m_wg / g + tid; r <= last_m / g; r += 64 * NW) mp = max(mp, q_pos[r]);
+    mp = (int)wave_max((float)mp);                     // positions < 2^24: exact in float
+    if (lane == 0 && mp >= 0) atomicMax(&s_max_pos, mp);
+  }
+  __syncthreads();
+  const int kv_len = s_max_pos + 1;
   const int n_tiles_all = (kv_len + BKV - 1) / BKV;
+  // the merge launch needs the same bound to know which pieces of the key range ran
+  if (gridDim.z > 1 && kvh == 0 && blockIdx.z == 0 && tid == 0) wg_tiles[gridDim.y - 1 - blockIdx.y] = n_tiles_all;
   // KV split: workgroup z of gridDim.z handles tiles [t_begin, n_tiles) of the causal range and
   // leaves un-normalised partial results (flash-decoding style) for the merge kernel
   const int t_begin = blockIdx.z * split_tiles;
@@ -317,7 +331,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
                                                          const int32_t *__restrict__ q_pos, int n_rows,
                                                          bf16 *__restrict__ o, int n_q_heads,
                                                          int n_kv_heads, int n_splits, int split_tiles,
-                                                         int wg_queries) {
+                                                         int wg_queries, const int32_t *__restrict__ wg_tiles) {
   constexpr int CG = DH / 4;                           // float4 channel groups per query
   const int g = n_q_heads / n_kv_heads, n_flat = n_rows * g;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -325,8 +339,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
   const int c = (int)(idx % CG);
   const long qh = idx / CG;                            // kvh * n_flat + m
   const int m = (int)(qh % n_flat), kvh = (int)(qh / n_flat);
-  const int last_m = min((m / wg_queries + 1) * wg_queries, n_flat) - 1;
-  const int n_tiles = (q_pos[last_m / g] + BKV) / BKV;
+  const int n_tiles = wg_tiles[m / wg_queries];      // key tiles of the query's workgroup
   const int ns = min(n_splits, (n_tiles + split_tiles - 1) / split_tiles);
   const float *ml = part_ml + qh * n_splits * 2;
   float mx = kNegBig;
@@ -429,12 +442,29 @@ static void attn_split_plan(int n_rows, int hq, int hkv, int dh, int n_tokens, i
   *n_splits = (max_tiles + *split_tiles - 1) / *split_tiles;
 }
 
+// scratch of a launch with ns key-range pieces: partial O, (max, sum) pairs, and one key-tile
+// count per query workgroup
+static size_t attn_scratch_floats(int n_rows, int hq, int hkv, int dh, int ns) {
+  const long n_flat = (long)n_rows * (hq / hkv);
+  return (size_t)n_rows * hq * ns * (dh + 2) + (size_t)((n_flat + ATT_WGQ - 1) / ATT_WGQ);
+}
+
 size_t attention_partial_floats(int dtype, int n_rows, int hq, int hkv, int dh, int n_tokens) {
   if (dtype == 0 || n_rows == 0) return 0;
   int ns, st;
   attn_split_plan(n_rows, hq, hkv, dh, n_tokens, &ns, &st);
   if (ns <= 1) return 0;
-  return (size_t)n_rows * hq * ns * (dh + 2);
+  return attn_scratch_floats(n_rows, hq, hkv, dh, ns);
+}
+
+// The same for ANY cache length: the piece count never exceeds what the row count alone allows.
+size_t attention_partial_floats_bound(int dtype, int n_rows, int hq, int hkv, int dh) {
+  if (dtype == 0 || n_rows == 0) return 0;
+  const long n_flat = (long)n_rows * (hq / hkv);
+  const long base = ((n_flat + ATT_WGQ - 1) / ATT_WGQ) * hkv;
+  const int ns = base < 128 ? (int)std::min<long>(32, (256 + base - 1) / base) : (base < 256 ? 2 : 1);
+  if (ns <= 1) return 0;
+  return attn_scratch_floats(n_rows, hq, hkv, dh, ns);
 }
 
 hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, const int32_t *q_pos, int n_rows,
@@ -456,26 +486,27 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
   const long n_flat = (long)n_rows * g;
   int n_splits, split_tiles;
   attn_split_plan(n_rows, hq, hkv, dh, n_tokens, &n_splits, &split_tiles);
-  if (n_splits > 1 && (!partial || partial_floats < (size_t)n_rows * hq * n_splits * (dh + 2))) {
+  if (n_splits > 1 && (!partial || partial_floats < attn_scratch_floats(n_rows, hq, hkv, dh, n_splits))) {
     n_splits = 1;                                    // no scratch: one workgroup walks all keys
     split_tiles = (n_tokens + BKV - 1) / BKV;
   }
   const int wgq = ATT_WGQ;
   float *part_o = partial;
   float *part_ml = partial ? partial + (size_t)n_rows * hq * n_splits * dh : nullptr;
+  int32_t *wg_tiles = partial ? reinterpret_cast<int32_t *>(part_ml + (size_t)n_rows * hq * n_splits * 2) : nullptr;
 #define CB_ATTN(DH_, NQB_, NW_)                                                                     \
   do {                                                                                              \
     constexpr int smem = ATT_S * 2 * BKV * DH_ * 2;                                                 \
-    static bool attr_set = false;                                                                   \
-    if (!attr_set) {                                                                                \
+    static std::once_flag once_;                                                                    \
+    std::call_once(once_, [] {                                                                      \
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<DH_, NQB_, NW_>),  \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);                  \
-      attr_set = true;                                                                              \
-    }                                                                                               \
+    });                                                                                             \
     hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_, NW_>),                                          \
                        dim3(hkv, (unsigned)((n_flat + wgq - 1) / wgq), n_splits), dim3(64 * NW_),   \
                        smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc, (const bf16 *)vc, \
-                       (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml, q_rows);      \
+                       (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml, q_rows,       \
+                       wg_tiles);                                                                   \
   } while (0)
   if (dh == 64) CB_ATTN(64, 1, ATT_NW);
   else CB_ATTN(128, 1, ATT_NW);
@@ -486,10 +517,10 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
   const dim3 mgrid((unsigned)((total + 255) / 256));
   if (dh == 64)
     hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
-                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq);
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq, wg_tiles);
   else
     hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
-                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq);
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq, wg_tiles);
   return hipGetLastError();
 }
 

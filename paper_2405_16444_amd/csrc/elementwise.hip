@@ -1,6 +1,6 @@
 // Bandwidth-bound kernels: positional re-alignment of cached keys (paper Sec. 4.3
-// footnote / Appendix A), RMSNorm, the per-token KV deviation (Sec. 4.1, Sec. 6),
-// the scatter of recomputed K/V rows into the fused cache (Sec. 4.2) and copies.
+// footnote / Appendix A), RMSNorm, the scatter of recomputed K/V rows into the fused
+// cache for a given selection (Sec. 4.2) and copies.
 #include "common.h"
 #include "kernels.h"
 #include <algorithm>
@@ -177,11 +177,15 @@ hipError_t launch_copy_rows_f32(const float *in, float *out, size_t n, hipStream
 
 // ---------------------------------------------------------------------------
 // RMSNorm: one block per row; the row (float) is read twice (second read hits L2).
+// With lo_off > 0 every value x is stored as the pair (hi, lo) = (T(x), T(x - hi)), lo lying
+// lo_off elements after hi: the Q/K/V projections multiply both parts, which gives them an
+// input accurate to float although the matrix cores take bf16 operands.
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h,
                                                       const T *__restrict__ gain,
-                                                      T *__restrict__ out, int d, float eps) {
+                                                      T *__restrict__ out, int ld_out, int lo_off, int d,
+                                                      float eps) {
   __shared__ float red[4];
   const float4 *row = reinterpret_cast<const float4 *>(h + (size_t)blockIdx.x * d);
   const int n4 = d / 4;
@@ -192,70 +196,28 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
   }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  T *orow = out + (size_t)blockIdx.x * d;
+  T *orow = out + (size_t)blockIdx.x * ld_out;
   for (int i = threadIdx.x; i < n4; i += 256) {
-    float4 v = row[i];
-    orow[4 * i + 0] = from_f32<T>(v.x * inv * to_f32(gain[4 * i + 0]));
-    orow[4 * i + 1] = from_f32<T>(v.y * inv * to_f32(gain[4 * i + 1]));
-    orow[4 * i + 2] = from_f32<T>(v.z * inv * to_f32(gain[4 * i + 2]));
-    orow[4 * i + 3] = from_f32<T>(v.w * inv * to_f32(gain[4 * i + 3]));
+    const float4 v = row[i];
+    const float x[4] = {v.x * inv * to_f32(gain[4 * i + 0]), v.y * inv * to_f32(gain[4 * i + 1]),
+                        v.z * inv * to_f32(gain[4 * i + 2]), v.w * inv * to_f32(gain[4 * i + 3])};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const T hi = from_f32<T>(x[j]);
+      orow[4 * i + j] = hi;
+      if (lo_off > 0) orow[lo_off + 4 * i + j] = from_f32<T>(x[j] - to_f32(hi));
+    }
   }
 }
-hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int n_rows, int d,
-                          float eps, hipStream_t s) {
+hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int ld_out, int lo_off,
+                          int n_rows, int d, float eps, hipStream_t s) {
   if (n_rows == 0) return hipSuccess;
   if (dtype == 0)
     hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n_rows), dim3(256), 0, s, h, (const float *)gain,
-                       (float *)out, d, eps);
+                       (float *)out, ld_out, lo_off, d, eps);
   else
     hipLaunchKernelGGL(rmsnorm_kernel<bf16>, dim3(n_rows), dim3(256), 0, s, h, (const bf16 *)gain,
-                       (bf16 *)out, d, eps);
-  return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
-// KV deviation: one wavefront per candidate token; 4 rows of kv_dim elements are
-// streamed once (new K, new V, cached K, cached V), squared differences summed in
-// float and reduced across the wavefront.
-// ---------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void deviation_kernel(const T *__restrict__ kvnew,
-                                                        const int32_t *__restrict__ row_pos,
-                                                        int n_cand, const T *__restrict__ kc,
-                                                        const T *__restrict__ vc, int kv_dim,
-                                                        float *__restrict__ dev) {
-  using V = Vec16<T>;
-  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (j >= n_cand) return;
-  const int lane = threadIdx.x & 63;
-  const int p = row_pos[j];
-  const int nv = kv_dim / V::N;
-  const V *kn = reinterpret_cast<const V *>(kvnew + (size_t)j * 2 * kv_dim);
-  const V *vn = kn + nv;
-  const V *ko = reinterpret_cast<const V *>(kc + (size_t)p * kv_dim);
-  const V *vo = reinterpret_cast<const V *>(vc + (size_t)p * kv_dim);
-  float acc = 0.f;
-  for (int i = lane; i < nv; i += 64) {
-    V a = kn[i], b = ko[i], c = vn[i], d = vo[i];
-#pragma unroll
-    for (int e = 0; e < V::N; ++e) {
-      float dk = a.get(e) - b.get(e), dv = c.get(e) - d.get(e);
-      acc += dk * dk + dv * dv;
-    }
-  }
-  acc = wave_sum(acc);
-  if (lane == 0) dev[j] = acc;
-}
-hipError_t launch_deviation(int dtype, const void *kvnew, const int32_t *row_pos, int n_cand,
-                            const void *kc, const void *vc, int kv_dim, float *dev, hipStream_t s) {
-  if (n_cand == 0) return hipSuccess;
-  dim3 grid((n_cand + 3) / 4);
-  if (dtype == 0)
-    hipLaunchKernelGGL(deviation_kernel<float>, grid, dim3(256), 0, s, (const float *)kvnew, row_pos,
-                       n_cand, (const float *)kc, (const float *)vc, kv_dim, dev);
-  else
-    hipLaunchKernelGGL(deviation_kernel<bf16>, grid, dim3(256), 0, s, (const bf16 *)kvnew, row_pos,
-                       n_cand, (const bf16 *)kc, (const bf16 *)vc, kv_dim, dev);
+                       (bf16 *)out, ld_out, lo_off, d, eps);
   return hipGetLastError();
 }
 

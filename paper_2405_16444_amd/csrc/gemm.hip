@@ -21,6 +21,9 @@
 //   EPI_F32    float output (+ residual)
 #include "common.h"
 #include "kernels.h"
+#include <algorithm>
+#include <cstdint>
+#include <mutex>
 
 namespace cb {
 
@@ -40,11 +43,25 @@ struct GemmParams {
   const int32_t *row_pos;
   int head_dim;
   int rope_half;        // rotary pairs (i, i + head_dim/2) instead of (2i, 2i+1)
-  int raw_partial;      // the main kernel only parks its sums in `partial`; the reduce launch applies the epilogue
+  int raw_partial;      // the main kernel only parks its sums in `partial`; the finish launch applies the epilogue
+  int a_lo_off;         // > 0: the activations are a (high, low) bf16 pair, the low parts a_lo_off elements after
+                        // the high parts of the same row; both are multiplied and their products added
   float *out_f32;
   const float *resid;
   const int32_t *resid_rows;
   float *partial;
+  // finish launch of EPI_SEG: squared distance of the stored new values of segment s from row
+  // dev_row[r] of dev_cache[s] (pitch = the segment's width), summed over the segments, for rows < n_dev
+  float *dev_out;
+  int n_dev;
+  const void *dev_cache[3];
+  const int32_t *dev_row;
+  // finish launch of EPI_F32: RMSNorm of the finished row (gain norm_gain, NULL: none) into norm_out
+  // (pitch norm_ld); norm_lo_off > 0 also stores the rounding remainder norm_lo_off elements further on
+  const void *norm_gain;
+  void *norm_out;
+  int norm_ld, norm_lo_off;
+  float norm_eps;
   int splits, k_per_split;
   // EPI_SWIGLU: workgroup ids >= tail_first share the tiles of the last, partly filled round of
   // workgroups, tail_splits of them per tile, each over tail_k_per_split of K
@@ -70,6 +87,14 @@ __device__ __forceinline__ const T *weight_row(const GemmParams &p, int gc, int 
   return reinterpret_cast<const T *>(p.w[s]) + (size_t)(gc - p.nb[s]) * p.K;
 }
 
+template <typename T> __device__ __forceinline__ float4 load4(const T *s);
+template <> __device__ __forceinline__ float4 load4<float>(const float *s) { return *reinterpret_cast<const float4 *>(s); }
+template <> __device__ __forceinline__ float4 load4<bf16>(const bf16 *s) {
+  const bf16x4 v = *reinterpret_cast<const bf16x4 *>(s);
+  return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+}
+// the value a float becomes when stored in the storage type
+template <typename T> __device__ __forceinline__ float as_stored(float v) { return to_f32(from_f32<T>(v)); }
 template <typename T> __device__ __forceinline__ void store4(T *d, float a, float b, float c, float e);
 template <> __device__ __forceinline__ void store4<float>(float *d, float a, float b, float c, float e) {
   *reinterpret_cast<float4 *>(d) = make_float4(a, b, c, e);
@@ -86,45 +111,56 @@ __device__ __forceinline__ int rope_partner_offset(const GemmParams &p, int gc) 
   return gc % p.head_dim < half ? half : -half;
 }
 
+// EPI_SEG: the values of output columns gc .. gc+3 of logical row gr after the rotary embedding
+// (a no-op for segments without it); *seg / *lcol receive the segment and the column inside it.
+// u: with p.rope_half, the values of columns gc + rope_partner_offset .. + 3.
+__device__ __forceinline__ float4 seg_rotate(float4 v, float4 u, int gr, int gc, const GemmParams &p, int *seg,
+                                             int *lcol) {
+  int s = 0;
+  if (p.n_seg > 1 && gc >= p.nb[1]) s = 1;
+  if (p.n_seg > 2 && gc >= p.nb[2]) s = 2;
+  const int lc = gc - p.nb[s];
+  *seg = s;
+  *lcol = lc;
+  if (!p.rope[s]) return v;
+  const int half = p.head_dim / 2;
+  float4 o;
+  if (p.rope_half) {
+    const int ch = lc % p.head_dim;
+    const bool first = ch < half;
+    const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (first ? ch : ch - half);
+    const float2 c0 = t[0], c1 = t[1], c2 = t[2], c3 = t[3];
+    if (first) {          // x0' = x0 cos - x1 sin, the partner holds x1
+      o.x = v.x * c0.x - u.x * c0.y;
+      o.y = v.y * c1.x - u.y * c1.y;
+      o.z = v.z * c2.x - u.z * c2.y;
+      o.w = v.w * c3.x - u.w * c3.y;
+    } else {              // x1' = x0 sin + x1 cos, the partner holds x0
+      o.x = u.x * c0.y + v.x * c0.x;
+      o.y = u.y * c1.y + v.y * c1.x;
+      o.z = u.z * c2.y + v.z * c2.x;
+      o.w = u.w * c3.y + v.w * c3.x;
+    }
+  } else {
+    const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (lc % p.head_dim) / 2;
+    const float2 c0 = t[0], c1 = t[1];
+    o.x = v.x * c0.x - v.y * c0.y;
+    o.y = v.x * c0.y + v.y * c0.x;
+    o.z = v.z * c1.x - v.w * c1.y;
+    o.w = v.z * c1.y + v.w * c1.x;
+  }
+  return o;
+}
+
 // One group of 4 adjacent output columns (gc .. gc+3) of logical row gr.
 // v: accumulated values; u: EPI_SWIGLU: the matching "up" values; EPI_SEG with p.rope_half: the
-// values of columns gc + rope_partner_offset .. + 3.
+// values of columns gc + rope_partner_offset .. + 3.  (EPI_F32 sums always go through `partial`
+// and are finished by resid_norm_finish_kernel.)
 template <typename T, int EPI>
 __device__ __forceinline__ void apply_epilogue(float4 v, float4 u, int gr, int gc, const GemmParams &p) {
   if (EPI == EPI_SEG) {
-    int s = 0;
-    if (p.n_seg > 1 && gc >= p.nb[1]) s = 1;
-    if (p.n_seg > 2 && gc >= p.nb[2]) s = 2;
-    const int lc = gc - p.nb[s];
-    if (p.rope[s] && p.rope_half) {
-      const int half = p.head_dim / 2, ch = lc % p.head_dim;
-      const bool first = ch < half;
-      const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (first ? ch : ch - half);
-      const float2 c0 = t[0], c1 = t[1], c2 = t[2], c3 = t[3];
-      float4 o;
-      if (first) {          // x0' = x0 cos - x1 sin, the partner holds x1
-        o.x = v.x * c0.x - u.x * c0.y;
-        o.y = v.y * c1.x - u.y * c1.y;
-        o.z = v.z * c2.x - u.z * c2.y;
-        o.w = v.w * c3.x - u.w * c3.y;
-      } else {              // x1' = x0 sin + x1 cos, the partner holds x0
-        o.x = u.x * c0.y + v.x * c0.x;
-        o.y = u.y * c1.y + v.y * c1.x;
-        o.z = u.z * c2.y + v.z * c2.x;
-        o.w = u.w * c3.y + v.w * c3.x;
-      }
-      v = o;
-    } else if (p.rope[s]) {
-      const int half = p.head_dim / 2;
-      const float2 *t = p.rope_tab + (size_t)p.row_pos[gr] * half + (lc % p.head_dim) / 2;
-      const float2 c0 = t[0], c1 = t[1];
-      float4 o;
-      o.x = v.x * c0.x - v.y * c0.y;
-      o.y = v.x * c0.y + v.y * c0.x;
-      o.z = v.z * c1.x - v.w * c1.y;
-      o.w = v.z * c1.y + v.w * c1.x;
-      v = o;
-    }
+    int s, lc;
+    v = seg_rotate(v, u, gr, gc, p, &s, &lc);
     const int dr = p.row_map[s] ? p.row_map[s][gr] : gr;
     store4<T>(reinterpret_cast<T *>(p.dst[s]) + (size_t)dr * p.ld[s] + lc, v.x, v.y, v.z, v.w);
   } else if (EPI == EPI_SWIGLU) {
@@ -134,13 +170,6 @@ __device__ __forceinline__ void apply_epilogue(float4 v, float4 u, int gr, int g
     o.z = v.z / (1.f + expf(-v.z)) * u.z;
     o.w = v.w / (1.f + expf(-v.w)) * u.w;
     store4<T>(reinterpret_cast<T *>(p.dst[0]) + (size_t)gr * p.ld[0] + gc, o.x, o.y, o.z, o.w);
-  } else {
-    if (p.resid) {
-      const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
-      const float4 q = *reinterpret_cast<const float4 *>(p.resid + (size_t)rr * p.N + gc);
-      v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
-    }
-    *reinterpret_cast<float4 *>(p.out_f32 + (size_t)gr * p.N + gc) = v;
   }
 }
 
@@ -318,9 +347,15 @@ __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tile
   }
 }
 
-template <int I, int NB, int EPI, int NWV>
+// HL (EPI_SEG only): the activations are (high, low) bf16 pairs.  The activation tile then holds
+// BM/2 logical rows twice -- their high parts in its first half, their low parts in its second --
+// so the wavefronts with wm = 0 multiply the high parts and those with wm = 1 the low parts of the
+// SAME output rows, and the two sets of sums are added in LDS before the epilogue.
+template <int I, int NB, int EPI, int NWV, bool HL = false>
 __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN), DMA_CP = BN + 4;
+  constexpr int BMO = HL ? BM / 2 : BM;                  // output rows per tile
+  static_assert(!HL || EPI == EPI_SEG, "operand pairs are for the Q/K/V projections only");
   constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128, W_RING = DMA_SA * A_STAGE;
   constexpr int WN = NWV / 2;                            // wavefronts as 2 x WN
   constexpr int NBW = 2 * NB / WN;                       // 32-column blocks per wavefront
@@ -352,7 +387,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     xcd_tile(j - z * per_z, xcd, tiles_m, nblk, &nt, &mt);
   }
   if (nt >= tiles_n) return;
-  const int m0 = mt * BM, n0 = nt * OUT_COLS;
+  const int m0 = mt * BMO, n0 = nt * OUT_COLS;
   const int kps = tail_z >= 0 ? p.tail_k_per_split : p.k_per_split;
   const int kb = (tail_z >= 0 ? tail_z : z) * kps;
   const int ke = min(p.K, kb + kps);
@@ -364,9 +399,10 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   for (int i = 0; i < LA; ++i) {
     const int r = (wave + NWV * i) * 8 + (lane >> 3);         // row of the activation tile
     const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
-    int ar = min(m0 + r, p.M - 1);
+    int ar = min(m0 + (HL ? r % BMO : r), p.M - 1);
     if (p.a_rows) ar = p.a_rows[ar];
-    src_a[i] = reinterpret_cast<const bf16 *>(p.a) + (size_t)ar * p.lda + chunk * 8 + kb;
+    src_a[i] = reinterpret_cast<const bf16 *>(p.a) + (size_t)ar * p.lda + chunk * 8 + kb +
+               (HL && r >= BMO ? p.a_lo_off : 0);
   }
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
@@ -419,7 +455,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     const int a_off = (wm * IH * 32) * 128, b_off = (wn * (BN / WN)) * 128;
     int blk_ok = 0;                                    // bit i: row block i of this wavefront holds a real row
 #pragma unroll
-    for (int i = 0; i < IH; ++i) blk_ok |= (m0 + (wm * IH + i) * 32 < p.M) << i;
+    for (int i = 0; i < IH; ++i) blk_ok |= (m0 + (HL ? i : wm * IH + i) * 32 < p.M) << i;
     blk_ok = __builtin_amdgcn_readfirstlane(blk_ok);
     bf16x8 fa[2][IH], fb[2][NBW];
     constexpr int NM = IH * NBW;                       // MFMAs per k-step per wavefront
@@ -546,22 +582,11 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
       for (int r = 0; r < 16; ++r) {
         const int gr = m0 + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
         if (gr >= p.M) continue;
-        if (p.splits > 1) {
-          float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
+        float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
 #pragma unroll
-          for (int jb = 0; jb < NBW; ++jb) {
-            const int gc = n0 + wn * (BN / WN) + jb * 32 + ln;
-            if (gc < p.N) prow[gc] = acc[i][jb][r];
-          }
-        } else {
-          const int rr = p.resid_rows ? p.resid_rows[gr] : gr;
-          const float *res = p.resid ? p.resid + (size_t)rr * p.N : nullptr;
-          float *orow = p.out_f32 + (size_t)gr * p.N;
-#pragma unroll
-          for (int jb = 0; jb < NBW; ++jb) {
-            const int gc = n0 + wn * (BN / WN) + jb * 32 + ln;
-            if (gc < p.N) orow[gc] = acc[i][jb][r] + (res ? res[gc] : 0.f);
-          }
+        for (int jb = 0; jb < NBW; ++jb) {
+          const int gc = n0 + wn * (BN / WN) + jb * 32 + ln;
+          if (gc < p.N) prow[gc] = acc[i][jb][r];
         }
       }
     }
@@ -571,6 +596,28 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   vm_wait<0>();
   __syncthreads();
   float *sC = reinterpret_cast<float *>(smem);
+  if (HL) {
+    // the sums over the high parts are parked first, the sums over the low parts added to them
+#pragma unroll
+    for (int part = 0; part < 2; ++part) {
+      if (wm == part) {
+#pragma unroll
+        for (int i = 0; i < IH; ++i)
+#pragma unroll
+          for (int jb = 0; jb < NBW; ++jb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int row = i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+              const int col = wn * (BN / WN) + jb * 32 + (lane & 31);
+              if (part == 0) sC[row * DMA_CP + col] = acc[i][jb][r];
+              else sC[row * DMA_CP + col] += acc[i][jb][r];
+            }
+      }
+      __syncthreads();
+    }
+    lds_epilogue<bf16, EPI, BN>(sC, DMA_CP, BMO, m0, n0, z, p);
+    return;
+  }
   // park and walk the tile in passes of at most 128 rows (LDS holds 128 x 260 floats)
   constexpr int PASSES = (I + 3) / 4;
 #pragma unroll
@@ -639,11 +686,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
   }
   bf16x8 ra[4], rb[4];
   const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-  auto gload = [&](int k0) {
+  // tile t of the k loop; with a (high, low) activation pair the K range is walked twice, the
+  // second time over the low parts
+  const int nt_all = p.a_lo_off > 0 ? 2 * nk : nk;
+  auto gload = [&](int t) {
+    const int lo = t >= nk;
+    const int k0 = kb + (t - lo * nk) * BK16;
+    const int a_adv = k0 + lo * p.a_lo_off;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const bool ok = k0 + kcol[i] < ke;
-      ra[i] = ok ? *reinterpret_cast<const bf16x8 *>(a_ptr[i] + k0) : zero;
+      ra[i] = ok ? *reinterpret_cast<const bf16x8 *>(a_ptr[i] + a_adv) : zero;
       rb[i] = ok ? *reinterpret_cast<const bf16x8 *>(b_ptr[i] + k0) : zero;
     }
   };
@@ -665,13 +718,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   if (nk > 0) {
-    gload(kb);
+    gload(0);
     sstore(0);
   }
   __syncthreads();
   const int frag_off = (lane & 31) * PITCH16 + 8 * (lane >> 5);
-  for (int t = 0; t < nk; ++t) {
-    if (t + 1 < nk) gload(kb + (t + 1) * BK16);
+  for (int t = 0; t < nt_all; ++t) {
+    if (t + 1 < nt_all) gload(t + 1);
     const bf16 *ca = sA + (t & 1) * BM16 * PITCH16 + (wm * 64) * PITCH16 + frag_off;
     const bf16 *cb_ = sB + (t & 1) * BN16 * PITCH16 + (wn * 64) * PITCH16 + frag_off;
 #pragma unroll
@@ -685,7 +738,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams p) {
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, b1, acc[1][1], 0, 0, 0);
     }
-    if (t + 1 < nk) sstore((t + 1) & 1);
+    if (t + 1 < nt_all) sstore((t + 1) & 1);
     __syncthreads();
   }
   // park the accumulators in LDS (the operand stages are dead after the last barrier)
@@ -757,29 +810,88 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
   lds_epilogue<float, EPI, BN32>(sC, CPITCH32, BM32, m0, n0, blockIdx.z, p);
 }
 
-// Adds the K-split partial sums in ascending split order and applies the epilogue.
-template <typename T, int EPI>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p) {
-  const size_t i4 = (size_t)blockIdx.x * 256 + threadIdx.x;
-  const size_t total4 = (size_t)p.M * p.N / 4;
-  if (i4 >= total4) return;
-  const size_t e = i4 * 4;
-  const int r = (int)(e / p.N), c = (int)(e % p.N);
+// ---------------------------------------------------------------------------
+// Finish launches: one workgroup per output row adds the parked partial sums in ascending split
+// order (fixed order, no atomics: bitwise reproducible) and completes the row.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float4 sum_splits(const GemmParams &p, size_t e) {
   float4 acc = make_float4(0, 0, 0, 0);
+  const size_t stride = (size_t)p.M * p.N;
   for (int z = 0; z < p.splits; ++z) {
-    const float4 v = *reinterpret_cast<const float4 *>(p.partial + (size_t)z * p.M * p.N + e);
+    const float4 v = *reinterpret_cast<const float4 *>(p.partial + z * stride + e);
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
-  float4 partner = acc;
-  if (EPI == EPI_SEG && p.rope_half) {
-    const size_t ep = (size_t)((long)e + rope_partner_offset(p, c));
-    partner = make_float4(0, 0, 0, 0);
-    for (int z = 0; z < p.splits; ++z) {
-      const float4 v = *reinterpret_cast<const float4 *>(p.partial + (size_t)z * p.M * p.N + ep);
-      partner.x += v.x; partner.y += v.y; partner.z += v.z; partner.w += v.w;
+  return acc;
+}
+
+// EPI_SEG rows: rotary embedding, conversion to the storage type, store (optionally through the
+// segment's row map) and -- for rows < n_dev -- the KV deviation of the row (Sec. 4.1, Sec. 6):
+// the squared distance of the values as stored from the cached row, over the segments that name a cache.
+template <typename T>
+__global__ __launch_bounds__(256) void seg_finish_kernel(GemmParams p) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const bool want_dev = p.dev_out != nullptr && r < p.n_dev;
+  const int crow = want_dev ? p.dev_row[r] : 0;
+  float dsum = 0.f;
+  for (int c = threadIdx.x * 4; c < p.N; c += 1024) {
+    const size_t e = (size_t)r * p.N + c;
+    const float4 acc = sum_splits(p, e);
+    float4 partner = acc;
+    if (p.rope_half) partner = sum_splits(p, (size_t)((long)e + rope_partner_offset(p, c)));
+    int s, lc;
+    const float4 v = seg_rotate(acc, partner, r, c, p, &s, &lc);
+    const int dr = p.row_map[s] ? p.row_map[s][r] : r;
+    store4<T>(reinterpret_cast<T *>(p.dst[s]) + (size_t)dr * p.ld[s] + lc, v.x, v.y, v.z, v.w);
+    if (want_dev && p.dev_cache[s]) {
+      const float4 old = load4<T>(reinterpret_cast<const T *>(p.dev_cache[s]) +
+                                  (size_t)crow * (p.nb[s + 1] - p.nb[s]) + lc);
+      const float d0 = as_stored<T>(v.x) - old.x, d1 = as_stored<T>(v.y) - old.y;
+      const float d2 = as_stored<T>(v.z) - old.z, d3 = as_stored<T>(v.w) - old.w;
+      dsum += d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3;
     }
   }
-  apply_epilogue<T, EPI>(acc, partner, r, c, p);
+  if (p.dev_out != nullptr) {              // uniform over the workgroup
+    dsum = block_sum_256(dsum, red);
+    if (want_dev && threadIdx.x == 0) p.dev_out[r] = dsum;
+  }
+}
+
+// EPI_F32 rows: h = sum of the partial sums + residual, stored as float; then, when a gain is
+// given, the RMSNorm of h in the storage type (the next projection's input), optionally as a
+// (high, low) pair.  A lane re-reads only elements it wrote itself.
+template <typename T>
+__global__ __launch_bounds__(256) void resid_norm_finish_kernel(GemmParams p) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const int rr = p.resid_rows ? p.resid_rows[r] : r;
+  float *orow = p.out_f32 + (size_t)r * p.N;
+  float ss = 0.f;
+  for (int c = threadIdx.x * 4; c < p.N; c += 1024) {
+    float4 v = sum_splits(p, (size_t)r * p.N + c);
+    if (p.resid) {
+      const float4 q = *reinterpret_cast<const float4 *>(p.resid + (size_t)rr * p.N + c);
+      v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+    }
+    *reinterpret_cast<float4 *>(orow + c) = v;
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  if (p.norm_gain == nullptr) return;      // uniform
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)p.N + p.norm_eps);
+  const T *gain = reinterpret_cast<const T *>(p.norm_gain);
+  T *nrow = reinterpret_cast<T *>(p.norm_out) + (size_t)r * p.norm_ld;
+  for (int c = threadIdx.x * 4; c < p.N; c += 1024) {
+    const float4 v = *reinterpret_cast<const float4 *>(orow + c);
+    const float x[4] = {v.x * inv * to_f32(gain[c]), v.y * inv * to_f32(gain[c + 1]),
+                        v.z * inv * to_f32(gain[c + 2]), v.w * inv * to_f32(gain[c + 3])};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const T hi = from_f32<T>(x[i]);
+      nrow[c + i] = hi;
+      if (p.norm_lo_off > 0) nrow[p.norm_lo_off + c + i] = from_f32<T>(x[i] - to_f32(hi));
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -787,13 +899,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p) {
 // ---------------------------------------------------------------------------
 struct GemmPlan {
   int kind;        // 0 float, 1 register-staged bf16, 2 direct-to-LDS bf16
-  int I, NB;       // kind 2: tile = 32I rows x 64NB columns
+  int I, NB;       // kind 2: the kernel's tile = 32I activation-tile rows x 64NB columns
   int nwv;         // kind 2: wavefronts per workgroup (4, or 8 = two per SIMD for the 256-column tiles)
-  int bm, out_cols, bk;
+  int hl;          // the activations are (high, low) pairs (bf16 EPI_SEG only)
+  int bm, out_cols, bk;   // bm: OUTPUT rows per tile (half the activation-tile rows with hl, kind 2)
   int tiles_m, tiles_n, splits, k_per_split;
   int tail_first, tail_splits, tail_k_per_split;   // EPI_SWIGLU tail sharing (tail_splits <= 1: none)
   long grid_ids;                                   // kind 2: workgroups of the main launch
   int xcd_split;                                   // kind 2: splits dealt to XCDs (see GemmParams)
+  int raw;                                         // sums are parked in `partial` and a finish launch completes them
   size_t partial_floats;
   bool bad;                                        // needs scratch the caller did not give
 };
@@ -817,13 +931,13 @@ static int pick_row_blocks(int M) {
 // slot of the chip is busy (a slot = one resident workgroup: two per CU for the tiles whose
 // rings fit twice into LDS, else one); a round that fills only part of the slots runs faster
 // per tile because fewer workgroups share the L2 -> LDS path; split partial sums cost their
-// round trip through memory.
+// round trip through memory.  max_splits caps the split (scratch the caller can spare).
 struct DmaShape { int I, NB; double t_full; };
 // Whole-prefill timings decided the candidate set: adding the 8x2, 4x4 and 6x4 tiles changed
 // nothing beyond noise, and 64-row tiles lost wherever more than 64 rows exist.
 static const DmaShape kDmaShapes[] = {{2, 2, 1.00}, {4, 2, 1.45}, {6, 2, 1.15}, {8, 4, 2.30}};
 
-static void pick_dma_plan(int M, int N, int K, GemmPlan *pl) {
+static void pick_dma_plan(int M, int N, int K, int max_splits, GemmPlan *pl) {
   const int k_tiles = K / DMA_BK;
   const double reduce_us = (double)M * N * 8.0 / 4.0e6;   // per split: written once, read once at ~4 TB/s
   double best = 1e30;
@@ -832,7 +946,7 @@ static void pick_dma_plan(int M, int N, int K, GemmPlan *pl) {
     const int bm = 32 * c.I, bn = 64 * c.NB;
     const int slots = dma_smem_bytes(c.I, bn) <= 80 * 1024 ? 512 : 256;
     const long tiles = (long)ceil_div(M, bm) * ceil_div(N, bn);
-    for (int sp = 1; sp <= 16; ++sp) {
+    for (int sp = 1; sp <= 16 && sp <= max_splits; ++sp) {
       if (sp > 1 && k_tiles / sp < 4) break;
       const long wgs = tiles * sp;
       const long full = wgs / slots;
@@ -845,9 +959,24 @@ static void pick_dma_plan(int M, int N, int K, GemmPlan *pl) {
   }
 }
 
-static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
+// The float kernel's 64-column tile does not hold a whole 128-channel head, so it cannot pair
+// channel i with i + head_dim/2 itself: it parks its sums and the finish launch rotates them.
+static bool needs_raw_partial(int dtype, int epi, int rope_half, int head_dim) {
+  return dtype == 0 && epi == EPI_SEG && rope_half && head_dim > BN32;
+}
+
+// Shape of one problem.  hl: (high, low) activation pairs; force_raw: the caller wants the finish
+// launch (deviation, or the float output's residual + norm); scratch_floats: what `partial` holds
+// (the K split is capped by it; SIZE_MAX when sizing).
+static GemmPlan make_plan(int dtype, int epi, int M, int N, int K, int hl, int force_raw, int rope_half,
+                          int head_dim, size_t scratch_floats) {
   GemmPlan pl = {};
   pl.splits = 1;
+  pl.hl = hl && dtype == 1 && epi == EPI_SEG;
+  pl.raw = force_raw || epi == EPI_F32 || needs_raw_partial(dtype, epi, rope_half, head_dim);
+  const size_t mn = (size_t)M * N;
+  const int max_splits = (int)std::min<size_t>(16, std::max<size_t>(1, scratch_floats / std::max<size_t>(1, mn)));
+  if (pl.raw && scratch_floats < mn) pl.bad = true;
   if (dtype == 0) {
     pl.kind = 0; pl.bm = BM32; pl.out_cols = epi == EPI_SWIGLU ? BN32 / 2 : BN32; pl.bk = BK32;
   } else if (K % DMA_BK != 0) {
@@ -863,11 +992,12 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
     if (c2 < c4) pl.NB = 2;
   } else {
     pl.kind = 2; pl.bk = DMA_BK;
-    pick_dma_plan(M, N, K, &pl);
+    // with operand pairs the activation tile holds every output row twice
+    pick_dma_plan(pl.hl ? 2 * M : M, N, K, max_splits, &pl);
   }
   if (pl.kind == 2) {
     pl.nwv = (pl.NB == 4 && pl.I >= 4) ? 8 : 4;
-    pl.bm = 32 * pl.I;
+    pl.bm = pl.hl ? 16 * pl.I : 32 * pl.I;
     pl.out_cols = (epi == EPI_SWIGLU ? 32 : 64) * pl.NB;
   }
   pl.tiles_m = ceil_div(M, pl.bm);
@@ -877,7 +1007,7 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   if (pl.kind == 1 && epi != EPI_SWIGLU && tiles < 256) {
     // smallest split that fills >= 90 % of a whole number of 256-workgroup rounds
     double best_eff = 0;
-    for (int sp = 1; sp <= 16; ++sp) {
+    for (int sp = 1; sp <= 16 && sp <= max_splits; ++sp) {
       if (sp > 1 && k_tiles / sp < 4) break;
       const long wgs = tiles * sp;
       const double eff = (double)wgs / (double)((wgs + 255) / 256 * 256);
@@ -887,7 +1017,8 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
   }
   pl.k_per_split = ceil_div(k_tiles, pl.splits) * pl.bk;
   pl.splits = ceil_div(K, pl.k_per_split);
-  pl.partial_floats = pl.splits > 1 ? (size_t)pl.splits * M * N : 0;
+  if (pl.splits > 1) pl.raw = 1;
+  pl.partial_floats = pl.raw ? (size_t)pl.splits * mn : 0;
   pl.tail_splits = 1;
   if (pl.kind == 2) {
     const long ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
@@ -908,7 +1039,8 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K) {
         const double t_tile = 0.3 * pl.I * (pl.NB == 4 ? 1.0 : 0.6);
         const double saved = (k_tiles - ceil_div(k_tiles, ts)) * t_tile;
         const double extra = (double)tail * ts * pl.bm * (64 * pl.NB) * 8.0 / 4.0e6 + 8.0;
-        if (saved > extra) {
+        const size_t need = (size_t)tail * ceil_div(K, ceil_div(k_tiles, ts) * pl.bk) * pl.bm * (64 * pl.NB);
+        if (saved > extra && need <= scratch_floats) {
           pl.tail_first = (int)full;
           pl.tail_k_per_split = ceil_div(k_tiles, ts) * pl.bk;
           pl.tail_splits = ceil_div(K, pl.tail_k_per_split);
@@ -928,16 +1060,10 @@ static int problem_n(const GemmArgs &g) {
   return n;
 }
 
-// The float kernel's 64-column tile does not hold a whole 128-channel head, so it cannot pair
-// channel i with i + head_dim/2 itself: it parks its sums and the reduce launch rotates them.
-static bool needs_raw_partial(int dtype, int epi, int rope_half, int head_dim) {
-  return dtype == 0 && epi == EPI_SEG && rope_half && head_dim > BN32;
-}
-
-size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int rope_half, int head_dim) {
+size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int hl, int force_raw, int rope_half,
+                           int head_dim) {
   if (M <= 0) return 0;
-  if (needs_raw_partial(dtype, epi, rope_half, head_dim)) return (size_t)M * N;
-  return make_plan(dtype, epi, M, N, K).partial_floats;
+  return make_plan(dtype, epi, M, N, K, hl, force_raw, rope_half, head_dim, SIZE_MAX).partial_floats;
 }
 
 static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
@@ -950,30 +1076,19 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
     p.w[i] = g.seg[i].w; p.dst[i] = g.seg[i].dst; p.ld[i] = g.seg[i].ld_dst;
     p.row_map[i] = g.seg[i].row_map; p.rope[i] = g.seg[i].rope;
     p.nb[i + 1] = p.nb[i] + (i < p.n_seg ? g.seg[i].n : 0);
+    p.dev_cache[i] = g.dev_out ? g.seg[i].dev_cache : nullptr;
   }
   p.N = problem_n(g);
   p.rope_tab = g.rope_tab; p.row_pos = g.row_pos; p.head_dim = g.head_dim;
   p.out_f32 = g.out_f32; p.resid = g.resid; p.resid_rows = g.resid_rows; p.partial = g.partial;
   p.rope_half = g.rope_half;
-  GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K);
-  if (needs_raw_partial(g.dtype, g.epi, g.rope_half, g.head_dim)) {
-    pl.partial_floats = (size_t)g.M * p.N;
-    pl.bad = !g.partial || g.partial_floats < pl.partial_floats;   // no other way to compute this
-    p.raw_partial = 1;
-    p.splits = 1;
-    p.k_per_split = pl.k_per_split;
-    return pl;
-  }
-  if (pl.partial_floats > 0 && (!g.partial || g.partial_floats < pl.partial_floats)) {
-    // no scratch: one pass over K
-    if (pl.kind == 2) pl.grid_ids = 8L * ceil_div(pl.tiles_n, 8) * pl.tiles_m;
-    pl.xcd_split = 0;
-    pl.splits = 1;
-    pl.k_per_split = ceil_div(g.K, pl.bk) * pl.bk;
-    pl.tail_splits = 1;
-    pl.tail_first = (int)pl.grid_ids;
-    pl.partial_floats = 0;
-  }
+  p.dev_out = g.dev_out; p.n_dev = g.n_dev; p.dev_row = g.dev_row;
+  p.norm_gain = g.norm_gain; p.norm_out = g.norm_out; p.norm_ld = g.norm_ld; p.norm_lo_off = g.norm_lo_off;
+  p.norm_eps = g.norm_eps;
+  const GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K, g.a_lo_off > 0, g.dev_out != nullptr, g.rope_half,
+                                g.head_dim, g.partial ? g.partial_floats : 0);
+  p.a_lo_off = pl.hl ? g.a_lo_off : 0;
+  p.raw_partial = pl.raw;
   p.splits = pl.splits;
   p.k_per_split = pl.k_per_split;
   p.tail_first = pl.tail_first; p.tail_splits = pl.tail_splits; p.tail_k_per_split = pl.tail_k_per_split;
@@ -981,24 +1096,49 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   return pl;
 }
 
-bool gemm_needs_reduce(const GemmArgs &g) {
+bool gemm_needs_finish(const GemmArgs &g) {
   if (g.M == 0) return false;
   GemmParams p;
   const GemmPlan pl = fill_params(g, &p);
-  return pl.splits > 1 || pl.tail_splits > 1 || p.raw_partial;
+  return pl.raw || pl.tail_splits > 1;
 }
 
-template <int I, int NB, int EPI, int NWV>
+// sets a kernel's dynamic LDS limit once per process, whichever host thread launches it first
+#define CB_LDS_LIMIT_ONCE(kernel_expr, bytes)                                                      \
+  do {                                                                                             \
+    static std::once_flag once_;                                                                   \
+    std::call_once(once_, [] {                                                                     \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel_expr),                       \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes));         \
+    });                                                                                            \
+  } while (0)
+
+template <int I, int NB, int EPI, int NWV, bool HL = false>
 static void launch_dma(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
   constexpr int smem = dma_smem_bytes(I, 64 * NB);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_dma_kernel<I, NB, EPI, NWV>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
+  CB_LDS_LIMIT_ONCE((&gemm_bf16_dma_kernel<I, NB, EPI, NWV, HL>), smem);
+  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI, NWV, HL>), dim3((unsigned)pl.grid_ids), dim3(64 * NWV), smem,
+                     s, p, pl.tiles_m, pl.tiles_n);
+}
+
+template <int EPI, bool HL>
+static void launch_dma_shape(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
+  if (pl.NB == 2) {
+    switch (pl.I) {
+      case 2: launch_dma<2, 2, EPI, 4, HL>(pl, p, s); break;
+      case 4: launch_dma<4, 2, EPI, 4, HL>(pl, p, s); break;
+      case 6: launch_dma<6, 2, EPI, 4, HL>(pl, p, s); break;
+      default: launch_dma<8, 2, EPI, 4, HL>(pl, p, s); break;
+    }
+  } else if (pl.nwv == 8) {
+    switch (pl.I) {
+      case 4: launch_dma<4, 4, EPI, 8, HL>(pl, p, s); break;
+      case 6: launch_dma<6, 4, EPI, 8, HL>(pl, p, s); break;
+      default: launch_dma<8, 4, EPI, 8, HL>(pl, p, s); break;
+    }
+  } else {
+    launch_dma<2, 4, EPI, 4, HL>(pl, p, s);
   }
-  hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI, NWV>), dim3((unsigned)pl.grid_ids), dim3(64 * NWV), smem, s,
-                     p, pl.tiles_m, pl.tiles_n);
 }
 
 template <int EPI>
@@ -1007,28 +1147,12 @@ static void launch_typed(const GemmPlan &pl, const GemmParams &p, hipStream_t s)
   if (pl.kind == 0) {
     hipLaunchKernelGGL(gemm_f32_kernel<EPI>, grid, dim3(256), 0, s, p);
   } else if (pl.kind == 1) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<EPI>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBf16);
-      attr_set = true;
-    }
+    CB_LDS_LIMIT_ONCE((&gemm_bf16_kernel<EPI>), kSmemBf16);
     hipLaunchKernelGGL(gemm_bf16_kernel<EPI>, grid, dim3(256), kSmemBf16, s, p);
-  } else if (pl.NB == 2) {
-    switch (pl.I) {
-      case 2: launch_dma<2, 2, EPI, 4>(pl, p, s); break;
-      case 4: launch_dma<4, 2, EPI, 4>(pl, p, s); break;
-      case 6: launch_dma<6, 2, EPI, 4>(pl, p, s); break;
-      default: launch_dma<8, 2, EPI, 4>(pl, p, s); break;
-    }
-  } else if (pl.nwv == 8) {
-    switch (pl.I) {
-      case 4: launch_dma<4, 4, EPI, 8>(pl, p, s); break;
-      case 6: launch_dma<6, 4, EPI, 8>(pl, p, s); break;
-      default: launch_dma<8, 4, EPI, 8>(pl, p, s); break;
-    }
+  } else if (EPI == EPI_SEG && pl.hl) {
+    launch_dma_shape<EPI_SEG, true>(pl, p, s);
   } else {
-    launch_dma<2, 4, EPI, 4>(pl, p, s);
+    launch_dma_shape<EPI, false>(pl, p, s);
   }
 }
 
@@ -1043,10 +1167,11 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
+hipError_t launch_gemm_finish(const GemmArgs &g, hipStream_t s) {
   if (g.M == 0) return hipSuccess;
   GemmParams p;
   const GemmPlan pl = fill_params(g, &p);
+  if (pl.bad) return hipErrorInvalidValue;
   if (pl.tail_splits > 1) {
     const dim3 tg((unsigned)((pl.grid_ids - pl.tail_first) / pl.tail_splits) * (pl.I / 2) * (pl.NB / 2));
 #define CB_TAIL(I_, NB_, W_) hipLaunchKernelGGL((swiglu_tail_kernel<I_, NB_, W_>), tg, dim3(256), 0, s, p, pl.tiles_m, pl.tiles_n)
@@ -1060,16 +1185,14 @@ hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s) {
 #undef CB_TAIL
     return hipGetLastError();
   }
-  if (pl.bad) return hipErrorInvalidValue;
-  if (pl.splits <= 1 && !p.raw_partial) return hipSuccess;
-  const size_t total4 = (size_t)g.M * p.N / 4;
-  const dim3 grid((unsigned)((total4 + 255) / 256));
-  if (g.dtype == 0) {
-    if (g.epi == EPI_SEG) hipLaunchKernelGGL((splitk_reduce_kernel<float, EPI_SEG>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((splitk_reduce_kernel<float, EPI_F32>), grid, dim3(256), 0, s, p);
+  if (!pl.raw) return hipSuccess;
+  const dim3 grid((unsigned)g.M);
+  if (g.epi == EPI_SEG) {
+    if (g.dtype == 0) hipLaunchKernelGGL(seg_finish_kernel<float>, grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(seg_finish_kernel<bf16>, grid, dim3(256), 0, s, p);
   } else {
-    if (g.epi == EPI_SEG) hipLaunchKernelGGL((splitk_reduce_kernel<bf16, EPI_SEG>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((splitk_reduce_kernel<bf16, EPI_F32>), grid, dim3(256), 0, s, p);
+    if (g.dtype == 0) hipLaunchKernelGGL(resid_norm_finish_kernel<float>, grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(resid_norm_finish_kernel<bf16>, grid, dim3(256), 0, s, p);
   }
   return hipGetLastError();
 }

@@ -14,13 +14,10 @@ hipError_t launch_realign(int dtype, void *const *k_layers_host, int n_layers,
                           const int32_t *chunk_offsets_host, int n_chunks, int kv_dim,
                           int head_dim, int rope_half, const float2 *rope_tab, hipStream_t s);
 hipError_t launch_to_f32(int dtype, const void *x, float *out, size_t n, hipStream_t s);
-// out[r] = rmsnorm(h[r]) * gain, r < n_rows; out has storage type.
-hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int n_rows,
-                          int d, float eps, hipStream_t s);
-// dev[j] = |kvnew[j] - (K[pos_j] | V[pos_j])|^2; kvnew rows are [K(kv_dim) | V(kv_dim)].
-hipError_t launch_deviation(int dtype, const void *kvnew, const int32_t *row_pos, int n_cand,
-                            const void *k_cache, const void *v_cache, int kv_dim, float *dev,
-                            hipStream_t s);
+// out[r] = rmsnorm(h[r]) * gain, r < n_rows; out has storage type and row pitch ld_out;
+// lo_off > 0: the rounding remainder of every value is stored lo_off elements after it.
+hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int ld_out, int lo_off,
+                          int n_rows, int d, float eps, hipStream_t s);
 // K[pos_out[i]] = kvnew[sel_rows[i]][:kv_dim], V[...] = kvnew[...][kv_dim:], i < m.
 hipError_t launch_scatter_kv(int dtype, const void *kvnew, const int32_t *sel_rows,
                              const int32_t *pos_out, int m, void *k_cache, void *v_cache,
@@ -31,9 +28,13 @@ hipError_t launch_copy_rows_f32(const float *in, float *out, size_t n, hipStream
 // ---- select.hip ------------------------------------------------------------
 // Keep the k largest of dev[0..n_cand) (ties -> lower index); sel_rows[0..k) = row_base + kept
 // row indices ascending, then the n_suffix rows row_base + n_cand ..; pos_out[i] = row_pos of
-// that row (row_pos indexed without row_base).  One workgroup.
-hipError_t launch_topk(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
-                       int32_t *sel_rows, int32_t *pos_out, int row_base, hipStream_t s);
+// that row and cache_row_out[i] (nullable) = its cache row (cache_row, NULL: row_pos; both indexed
+// without row_base).  With kvnew != NULL the same launch copies the kept rows' new K/V
+// (kvnew[row_base + i] = [K | V], kv_row_bytes each, a multiple of 16) into rows cache_row of kc / vc.
+hipError_t launch_topk_scatter(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
+                               const int32_t *cache_row, int32_t *sel_rows, int32_t *pos_out,
+                               int32_t *cache_row_out, int row_base, const void *kvnew, void *kc, void *vc,
+                               int kv_row_bytes, hipStream_t s);
 // out[i] = src[idx[i]], i < n.
 hipError_t launch_gather_i32(const int32_t *src, const int32_t *idx, int n, int32_t *out, hipStream_t s);
 // Same outputs from a given ascending list of positions (lower-bound search in row_pos).
@@ -49,12 +50,15 @@ struct GemmSeg {
   int ld_dst;              // destination row pitch in elements
   const int32_t *row_map;  // EPI_SEG: destination row = row_map[r] (NULL: r)
   int rope;                // EPI_SEG: rotate adjacent column pairs by row_pos[r]
+  const void *dev_cache;   // EPI_SEG with dev_out: cache [*, n] this segment's new values are compared with (NULL: none)
 };
 struct GemmArgs {
   int dtype;
   const void *a;           // [*, K] row-major activations (storage type), pitch lda
   int lda;
   const int32_t *a_rows;   // gather: logical row r reads a[a_rows[r]] (NULL: r)
+  int a_lo_off;            // bf16 EPI_SEG: > 0 = every row also holds the rounding remainders of its K values,
+                           // a_lo_off elements further on; both parts are multiplied (float-accurate input)
   int M, K;
   int epi;
   int n_seg;               // EPI_SEG: 1..3 segments; EPI_SWIGLU: seg[0]=gate, seg[1]=up
@@ -67,26 +71,43 @@ struct GemmArgs {
   float *out_f32;          // EPI_F32: [M, n] float output, pitch n
   const float *resid;      // EPI_F32: added to the output; row r reads resid[resid_rows[r]]
   const int32_t *resid_rows;
-  float *partial;          // split-K scratch (gemm_partial_floats); too small or NULL: no split
+  // EPI_F32: RMSNorm of the finished rows in the storage type (norm_gain NULL: none), pitch norm_ld;
+  // norm_lo_off > 0: the rounding remainders are stored norm_lo_off elements after the values
+  const void *norm_gain;
+  void *norm_out;
+  int norm_ld, norm_lo_off;
+  float norm_eps;
+  // EPI_SEG: dev_out[r] (r < n_dev) = squared distance of the row's stored new values from row
+  // dev_row[r] of the segments' dev_cache arrays (NULL: no deviation)
+  float *dev_out;
+  int n_dev;
+  const int32_t *dev_row;
+  float *partial;          // scratch for parked sums (gemm_partial_floats); the K split is capped by it
   size_t partial_floats;
 };
-// Floats of split-K scratch a problem of this shape uses (0 when it is not split); N is the
-// total number of output columns (d_ff for EPI_SWIGLU).  For workspace sizing.
-size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int rope_half = 0, int head_dim = 0);
-// Main kernel.  A problem that was split along K (gemm_needs_reduce) leaves raw partial sums
-// in g.partial and must be completed by launch_gemm_reduce on the same stream.
+// Floats of scratch a problem of this shape parks its sums in when the scratch is not the limit
+// (0 when the main kernel finishes the outputs itself); N is the total number of output columns
+// (d_ff for EPI_SWIGLU); hl: (high, low) activation pairs; force_raw: a deviation is wanted.
+// For workspace sizing.
+size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int hl, int force_raw, int rope_half,
+                           int head_dim);
+// Main kernel.  EPI_F32 problems, problems with a deviation, and problems split along K
+// (gemm_needs_finish) leave raw sums in g.partial and must be completed by launch_gemm_finish on
+// the same stream.  EPI_F32 and deviation problems REQUIRE partial_floats >= M * N.
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
-bool gemm_needs_reduce(const GemmArgs &g);
-hipError_t launch_gemm_reduce(const GemmArgs &g, hipStream_t s);
+bool gemm_needs_finish(const GemmArgs &g);
+hipError_t launch_gemm_finish(const GemmArgs &g, hipStream_t s);
 
 // ---- attention.hip ---------------------------------------------------------
 // o[r, h, :] = softmax_{j <= q_pos[r]}(q[r,h,:] . K[j, h/g, :] / sqrt(dh)) V[j, h/g, :]
 // o: [n_rows, Hq, dh] storage type; q: row r is read at q[q_rows[r]] (q_rows NULL: q[r]);
-// caches [*, Hkv, dh]; q_pos ascending.
+// caches [*, Hkv, dh]; q_pos in any order (ascending positions give the best key-range skipping).
 // n_tokens: rows of the caches (upper bound of q_pos + 1).  partial: scratch for the KV split
 // used when there are few query rows (attention_partial_floats floats; NULL or too small: no split).
 size_t attention_partial_floats(int dtype, int n_rows, int n_q_heads, int n_kv_heads, int head_dim,
                                 int n_tokens);
+// upper bound of the above over every n_tokens (for workspace sizing)
+size_t attention_partial_floats_bound(int dtype, int n_rows, int n_q_heads, int n_kv_heads, int head_dim);
 hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, const int32_t *q_pos, int n_rows,
                             const void *k_cache, const void *v_cache, void *o, int n_q_heads,
                             int n_kv_heads, int head_dim, int n_tokens, float *partial,

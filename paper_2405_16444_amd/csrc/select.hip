@@ -1,6 +1,6 @@
 // HKVD selection (paper Sec. 4.3): keep the k tokens with the largest KV deviation.
 //
-// One 1024-lane workgroup.  Deviations are sums of squares (>= +0, finite), so the
+// 1024-lane workgroups.  Deviations are sums of squares (>= +0, finite), so the
 // unsigned order of their IEEE bit patterns is their numeric order.  Four 8-bit
 // radix passes over LDS histograms find the bit pattern of the k-th largest value
 // and how many entries equal to it must still be taken; one ordered compaction
@@ -9,6 +9,7 @@
 // it -- which is "ties go to the lower position".
 #include "common.h"
 #include "kernels.h"
+#include <algorithm>
 
 namespace cb {
 
@@ -35,15 +36,24 @@ __device__ __forceinline__ int block_excl_count(bool flag, int *wave_tot, int *t
   return before + excl;
 }
 
-__global__ __launch_bounds__(kSelThreads) void topk_kernel(const float *__restrict__ dev, int n, int k,
-                                                           int n_suffix,
-                                                           const int32_t *__restrict__ row_pos,
-                                                           int32_t *__restrict__ sel_rows,
-                                                           int32_t *__restrict__ pos_out, int row_base) {
+// Selection and cache update in one launch.  Every workgroup of the grid runs the same selection
+// (the keys are few and sit in L2), workgroup 0 writes the index lists, and the new K/V of the
+// kept rows (Sec. 6: only the kept tokens' KV is updated) are copied into the cache by workgroup
+// o % gridDim.x, o being the row's rank in the output -- so the copies are spread over the chip
+// without a second launch.  kvnew rows are [K | V] of vec_per_row 16-byte vectors each, indexed by
+// row_base + candidate index; cache_row (NULL: row_pos) names each candidate's row in kc / vc.
+constexpr int kSelList = 1024;          // kept rows one workgroup may have to copy
+__global__ __launch_bounds__(kSelThreads) void topk_scatter_kernel(
+    const float *__restrict__ dev, int n, int k, int n_suffix, const int32_t *__restrict__ row_pos,
+    const int32_t *__restrict__ cache_row, int32_t *__restrict__ sel_rows, int32_t *__restrict__ pos_out,
+    int32_t *__restrict__ cache_row_out, int row_base, const uint4 *__restrict__ kvnew, uint4 *__restrict__ kc,
+    uint4 *__restrict__ vc, int vec_per_row) {
   __shared__ unsigned hist[256];
   __shared__ unsigned s_prefix, s_need;
   __shared__ int wave_tot[kSelWaves];
+  __shared__ int2 list[kSelList];
   const int tid = threadIdx.x;
+  const int G = gridDim.x, wg = blockIdx.x;
   const unsigned *keys = reinterpret_cast<const unsigned *>(dev);
 
   unsigned prefix = 0, mask = 0, need = (unsigned)k;
@@ -94,6 +104,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float *__restri
     need = 0;
   }
   // ordered compaction
+  auto emit = [&](int o, int i) {            // output rank o is candidate / suffix row i of this request
+    const int cr = cache_row ? cache_row[i] : row_pos[i];
+    if (wg == 0) {
+      sel_rows[o] = row_base + i;
+      pos_out[o] = row_pos[i];
+      if (cache_row_out) cache_row_out[o] = cr;
+    }
+    if (o % G == wg) list[o / G] = make_int2(row_base + i, cr);
+  };
   int eq_seen = 0, out_base = 0;
   for (int base = 0; base < n; base += kSelThreads) {
     const int i = base + tid;
@@ -105,24 +124,39 @@ __global__ __launch_bounds__(kSelThreads) void topk_kernel(const float *__restri
     int eq_rank = eq_seen + block_excl_count(eq, wave_tot, &tot_eq);
     const bool take = gt || (eq && (unsigned)eq_rank < need);
     int o = out_base + block_excl_count(take, wave_tot, &tot_take);
-    if (take) {
-      sel_rows[o] = row_base + i;
-      pos_out[o] = row_pos[i];
-    }
+    if (take) emit(o, i);
     eq_seen += tot_eq;
     out_base += tot_take;
   }
-  for (int i = tid; i < n_suffix; i += kSelThreads) {
-    sel_rows[k + i] = row_base + n + i;
-    pos_out[k + i] = row_pos[n + i];
+  for (int i = tid; i < n_suffix; i += kSelThreads) emit(k + i, n + i);
+  if (kvnew == nullptr) return;              // uniform: selection only
+  __syncthreads();
+  const int n_out = k + n_suffix;
+  const int mine = wg < n_out ? (n_out - wg + G - 1) / G : 0;
+  const int per_row = 2 * vec_per_row;
+  for (int idx = tid; idx < mine * per_row; idx += kSelThreads) {
+    const int2 e = list[idx / per_row];
+    const int c = idx % per_row;
+    const uint4 v = kvnew[(size_t)e.x * per_row + c];
+    if (c < vec_per_row) kc[(size_t)e.y * vec_per_row + c] = v;
+    else vc[(size_t)e.y * vec_per_row + (c - vec_per_row)] = v;
   }
 }
 
-hipError_t launch_topk(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
-                       int32_t *sel_rows, int32_t *pos_out, int row_base, hipStream_t s) {
-  if (k + n_suffix == 0) return hipSuccess;
-  hipLaunchKernelGGL(topk_kernel, dim3(1), dim3(kSelThreads), 0, s, dev, n_cand, k, n_suffix, row_pos,
-                     sel_rows, pos_out, row_base);
+hipError_t launch_topk_scatter(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
+                               const int32_t *cache_row, int32_t *sel_rows, int32_t *pos_out,
+                               int32_t *cache_row_out, int row_base, const void *kvnew, void *kc, void *vc,
+                               int kv_row_bytes, hipStream_t s) {
+  const int n_out = k + n_suffix;
+  if (n_out == 0) return hipSuccess;
+  int G = 1;
+  if (kvnew) {
+    G = std::min(128, (n_out + 3) / 4);
+    G = std::max(G, (n_out + kSelList - 1) / kSelList);
+  }
+  hipLaunchKernelGGL(topk_scatter_kernel, dim3(G), dim3(kSelThreads), 0, s, dev, n_cand, k, n_suffix, row_pos,
+                     cache_row, sel_rows, pos_out, cache_row_out, row_base, (const uint4 *)kvnew, (uint4 *)kc,
+                     (uint4 *)vc, kv_row_bytes / 16);
   return hipGetLastError();
 }
 
