@@ -139,6 +139,24 @@ int cb_fuse_layer(cb_ctx *ctx, int32_t layer, const cb_layer_weights *weights /*
                   const int32_t *forced_sel, float *h_out, int32_t *pos_out, float *dev_out,
                   void *workspace, size_t workspace_bytes, void *stream);
 
+/* cb_fuse_layer for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, results and validation, minus the
+ * workspace -- the layer's intermediates live in an array of CB_STATIC_SCRATCH_BYTES built into the
+ * library (one copy per GPU, held until the process ends).  The call allocates nothing on the device or
+ * through the HIP runtime.  A call whose cb_layer_workspace_bytes(ctx, n_rows) exceeds CB_STATIC_SCRATCH_BYTES is
+ * refused with CB_EWORKSPACE before any launch; the ctx must have been created on the device that is
+ * current (else CB_EINVAL).  Every call on a GPU shares that GPU's array: calls that overlap in time on
+ * one GPU (two streams, two ctx objects, two threads) race on it.  The array keeps the last call's
+ * contents; nothing in it has to start at zero, every region is written before it is read.  Per-launch
+ * timing (cb_profile_enable) is suspended during the call. */
+#define CB_STATIC_SCRATCH_BYTES (128u << 20)
+size_t cb_static_scratch_bytes(void);
+int cb_fuse_layer_static(cb_ctx *ctx, int32_t layer, const cb_layer_weights *weights /*HOST*/,
+                         const float *h_in, const int32_t *row_pos, int32_t n_rows, int32_t n_suffix,
+                         void *k_cache, void *v_cache, int32_t n_tokens_total, int32_t k_keep,
+                         const int32_t *forced_sel, float *h_out, int32_t *pos_out, float *dev_out,
+                         void *stream);
+
 /* Whole fusing pass (Sec. 4; Sec. 5.1 "fusor"): cb_realign_rope on layers 1 .. L-1 (layer 0
  * keeps, i.e. recomputes, every context row, so its pre-computed K/V is never read), then
  * cb_fuse_layer for layers 0 .. L-1, each layer's survivors feeding the next.

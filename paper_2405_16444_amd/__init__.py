@@ -7,7 +7,7 @@ raises ImportError (there is no CPU or torch fallback)."""
 
 _BINDING_NAMES = ("Context", "CacheBlendError", "cb_create", "cb_destroy", "cb_strerror",
                   "cb_layer_workspace_bytes", "cb_prefill_workspace_bytes", "cb_default_schedule",
-                  "cb_realign_rope", "cb_fuse_layer", "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_batched_workspace_bytes",
+                  "cb_realign_rope", "cb_fuse_layer", "cb_static_scratch_bytes", "cb_fuse_layer_static", "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_batched_workspace_bytes",
                   "cb_fuse_prefill_batched", "cb_first_token",
                   "cb_recompute_delay", "cb_load_delay", "cb_pick_recompute_ratio",
                   "cb_pick_storage_device", "cb_profile_enable",

@@ -61,6 +61,10 @@ def _load():
     lib.cb_realign_rope.argtypes = [vp, C.POINTER(vp), i32, i32, C.POINTER(i32), i32, vp]
     lib.cb_fuse_layer.argtypes = [vp, i32, C.POINTER(_LayerWeights), vp, vp, i32, i32, vp, vp, i32, i32,
                                   vp, vp, vp, vp, vp, sz, vp]
+    lib.cb_static_scratch_bytes.argtypes = []
+    lib.cb_static_scratch_bytes.restype = sz
+    lib.cb_fuse_layer_static.argtypes = [vp, i32, C.POINTER(_LayerWeights), vp, vp, i32, i32, vp, vp, i32, i32,
+                                         vp, vp, vp, vp, vp]
     lib.cb_fuse_prefill.argtypes = [vp, C.POINTER(_LayerWeights), vp, C.POINTER(i32), i32, i32,
                                     C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(vp), vp,
                                     C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
@@ -91,7 +95,7 @@ def _load():
 _lib = _load()
 EXPORTS = ("cb_create", "cb_destroy", "cb_strerror", "cb_layer_workspace_bytes",
            "cb_prefill_workspace_bytes", "cb_default_schedule", "cb_realign_rope", "cb_fuse_layer",
-           "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_batched_workspace_bytes",
+           "cb_static_scratch_bytes", "cb_fuse_layer_static", "cb_fuse_prefill", "cb_fuse_prefill_pipelined", "cb_batched_workspace_bytes",
            "cb_fuse_prefill_batched", "cb_first_token", "cb_recompute_delay", "cb_load_delay",
            "cb_pick_recompute_ratio", "cb_pick_storage_device", "cb_profile_enable", "cb_profile_read")
 
@@ -222,6 +226,39 @@ def cb_fuse_layer(ctx: Context, layer: int, weights: Dict[str, torch.Tensor], h_
                               _ptr(k_cache), _ptr(v_cache), k_cache.shape[0], k_keep, _ptr(forced_sel),
                               _ptr(h_out), _ptr(pos_out), _ptr(dev), _ptr(workspace), workspace.numel(),
                               _stream(stream)), "cb_fuse_layer")
+    return h_out[:n_out], pos_out[:n_out], dev
+
+
+def cb_static_scratch_bytes() -> int:
+    return int(_lib.cb_static_scratch_bytes())
+
+
+def cb_fuse_layer_static(ctx: Context, layer: int, weights: Dict[str, torch.Tensor], h_in: torch.Tensor,
+                         row_pos: torch.Tensor, n_suffix: int, k_cache: torch.Tensor, v_cache: torch.Tensor,
+                         k_keep: int, h_out: torch.Tensor, pos_out: torch.Tensor,
+                         forced_sel: Optional[torch.Tensor] = None, dev: Optional[torch.Tensor] = None,
+                         stream=None):
+    """cb_fuse_layer on the library's built-in scratch array.  The caller passes every output
+    (h_out float [>= k_keep + n_suffix, d], pos_out int32, dev float [n_rows - n_suffix] or None):
+    nothing is allocated here or in the library."""
+    n_rows = h_in.shape[0]
+    n_out = k_keep + n_suffix
+    assert h_in.dtype == torch.float32 and h_in.is_contiguous() and h_in.shape[1] == ctx.model.d_model
+    assert row_pos.dtype == torch.int32 and row_pos.shape == (n_rows,) and row_pos.is_contiguous()
+    assert k_cache.dtype == ctx.dtype and v_cache.dtype == ctx.dtype
+    assert k_cache.is_contiguous() and v_cache.is_contiguous() and k_cache.shape == v_cache.shape
+    assert h_out.dtype == torch.float32 and h_out.is_contiguous() and h_out.shape[0] >= n_out
+    assert h_out.shape[1] == ctx.model.d_model
+    assert pos_out.dtype == torch.int32 and pos_out.is_contiguous() and pos_out.numel() >= n_out
+    if forced_sel is not None:
+        assert forced_sel.dtype == torch.int32 and forced_sel.numel() == k_keep and forced_sel.is_contiguous()
+    if dev is not None:
+        assert dev.dtype == torch.float32 and dev.is_contiguous() and dev.numel() >= n_rows - n_suffix
+    w = _weights_struct(weights, ctx.dtype, ctx.device)
+    _check(_lib.cb_fuse_layer_static(ctx._h, layer, C.byref(w), _ptr(h_in), _ptr(row_pos), n_rows, n_suffix,
+                                     _ptr(k_cache), _ptr(v_cache), k_cache.shape[0], k_keep, _ptr(forced_sel),
+                                     _ptr(h_out), _ptr(pos_out), _ptr(dev), _stream(stream)),
+           "cb_fuse_layer_static")
     return h_out[:n_out], pos_out[:n_out], dev
 
 

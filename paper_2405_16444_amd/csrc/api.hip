@@ -11,6 +11,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -36,9 +37,32 @@ struct cb_ctx {
   std::vector<hipEvent_t> free_events;
   std::vector<hipEvent_t> load_events;   // pipelined loading: [0] = entry fence, [1 + l] = layer l landed
   mutable std::vector<size_t> partial_memo;   // [rows] -> scratch floats layer calls with <= rows rows can use
+  void *static_scratch;                  // this device's copy of the built-in scratch array (cb_fuse_layer_static)
 };
 
+// Built-in workspace of cb_fuse_layer_static, for callers that cannot allocate: one copy per GPU
+// that loads the library, held until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress -- it is never passed to a kernel or a runtime call as if it were a
+// device address; static_scratch_of() resolves the current device's copy once.
+static __device__ __align__(256) unsigned char scratch[CB_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];            // per device: address of its copy of `scratch`
+
+// Address of `scratch` on `device`, which must be the current device.  NULL on failure.
+void *static_scratch_of(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[device] = ptr;
+  }
+  return g_scratch_ptr[device];
+}
 
 size_t esize(const cb_ctx *c) { return c->m.dtype == CB_BF16 ? 2 : 4; }
 
@@ -380,6 +404,8 @@ int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out) {
   c->profiling = false;
   c->rope_tab = nullptr;
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CB_EHIP; }
+  c->static_scratch = static_scratch_of(c->device);
+  if (!c->static_scratch) { delete c; return CB_EHIP; }
   // rotary table in double precision on the host: (cos, sin)(p * theta^(-2i/dh)) (Appendix A)
   const int half = m.head_dim / 2;
   std::vector<float2> tab;
@@ -492,6 +518,27 @@ int cb_fuse_layer(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const flo
   const Seg seg = {n_rows, n_suffix, k_keep, n_tokens_total};
   return fuse_layer_impl(c, w, h_in, row_pos, nullptr, &seg, 1, 0, k_cache, v_cache, forced_sel, h_out, pos_out,
                          nullptr, dev_out, ws, (hipStream_t)stream, false, nullptr);
+}
+
+size_t cb_static_scratch_bytes(void) { return CB_STATIC_SCRATCH_BYTES; }
+
+int cb_fuse_layer_static(cb_ctx *c, int32_t layer, const cb_layer_weights *w, const float *h_in,
+                         const int32_t *row_pos, int32_t n_rows, int32_t n_suffix, void *k_cache,
+                         void *v_cache, int32_t n_tokens_total, int32_t k_keep, const int32_t *forced_sel,
+                         float *h_out, int32_t *pos_out, float *dev_out, void *stream) {
+  if (!c) return CB_ENULL;
+  if (n_rows > 0 && cb_layer_workspace_bytes(c, n_rows) > CB_STATIC_SCRATCH_BYTES) return CB_EWORKSPACE;
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return CB_EHIP;
+  if (device != c->device) return CB_EINVAL;   // the ctx's device holds the scratch this call would use
+  // per-launch timing creates events; this entry point creates nothing
+  const bool profiling = c->profiling;
+  c->profiling = false;
+  const int st = cb_fuse_layer(c, layer, w, h_in, row_pos, n_rows, n_suffix, k_cache, v_cache, n_tokens_total,
+                               k_keep, forced_sel, h_out, pos_out, dev_out, c->static_scratch,
+                               CB_STATIC_SCRATCH_BYTES, stream);
+  c->profiling = profiling;
+  return st;
 }
 
 namespace {
