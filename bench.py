@@ -7,16 +7,21 @@ shape (weights, inputs and the pre-computed chunk caches are resident in HBM bef
 the timed region; the caches are restored from a pristine copy between steps, outside
 the timed region, because the path fuses them in place).
 
-Prints ONE JSON line: the whole-call throughput in recomputed token-layers per second
-(sum over layers of the rows that went through attention + MLP, divided by the call
-time = TTFT), the roofline position of the dominant kernel class (the MFMA GEMMs)
-measured with HIP events inside the library, and the CPU oracle timed on a bounded
-slice of the same workload."""
+Prints ONE JSON line.  Headline workload (default: the Llama-70B-shaped request, the
+largest single-GPU configuration): `value` = token-layers recomputed per second on the
+selective layers (sum over layers >= 1 of the rows kept, divided by the GPU time of those
+layers), whole-call TTFT as median / p10 / p90 beside it, the roofline position of the
+dominant kernel class (the MFMA GEMMs) measured with HIP events inside the library, and
+the CPU oracle timed on a bounded sample of the same workload.  The other workloads of
+the configuration list follow in `workloads` (fewer steps each)."""
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,13 +29,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}
-
-# Bytes moved between L2 and the memory fabric per GEMM launch (average over the GEMM launches of
-# one step), from two rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled
-# by what the same counter reads for kernels of known size in the same run (FETCH_SIZE x 1.999,
-# WRITE_SIZE x 1.000); summary under profiles/.  Keyed by (workload, schedule, layers, ratio):
-# any other run reports null.
-PMC_TRAFFIC_BYTES_PER_GEMM_LAUNCH = {("mistral7b", "gradual", 32, 0.15): 216.7e6}
+METRIC = "hkvd_recompute_tokens_per_s (token-layers recomputed per second on the selective layers of one fused prefill)"
+# (workload, ratio or None = the workload's own) measured after the headline, fewer steps each
+EXTRA = [("mistral7b", None), ("yi34b", 0.05), ("yi34b", 0.15), ("yi34b", 0.30), ("long32k", None),
+         ("long_ragged", None)]
 
 
 def parse():
@@ -38,12 +40,16 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="mistral7b")
+    ap.add_argument("--workload", default="llama70b")
     ap.add_argument("--layers", type=int, default=0, help="reduce depth (0 = the workload's own)")
     ap.add_argument("--ratio", type=float, default=None)
     ap.add_argument("--flat", action="store_true", help="flat schedule instead of gradual filtering")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--full-oracle", action="store_true",
+                    help="cpu_baseline = the oracle on the WHOLE workload (chunk prefill + fusing pass); "
+                         "seconds for `tiny`, tens of minutes for the Mistral-7B shape")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="headline workload only")
     ap.add_argument("--batch", type=int, default=1,
                     help="requests fused per call (cb_fuse_prefill_batched when > 1; distinct inputs per request)")
     ap.add_argument("--no-host-load", action="store_true",
@@ -64,36 +70,109 @@ def attention_flops(model, sel_sets, n_ctx, n_suffix):
     return total
 
 
-def cpu_baseline(w, keep):
-    """The oracle as it stands on layers 0-1 of the workload (a full layer, then the first
-    selective layer with its check), real widths, synthetic inputs from the same generator."""
+def kernel_sources_sha16():
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2405_16444_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def pmc_traffic(workload_name, schedule, ratio):
+    """HBM bytes per GEMM launch from the rocprofv3 --pmc summary kept under profiles/ for this
+    workload -- used only while the kernel sources are the ones that summary was taken with
+    (it records their hash); otherwise null."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload_name}_pmc_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None, "no --pmc summary for this workload under profiles/"
+    text = open(path).read()
+    m = re.search(r"traffic_bytes_per_gemm_launch:\s*([0-9.eE+]+)\s+schedule=(\w+)\s+ratio=([0-9.]+)\s+csrc_sha16=(\w+)", text)
+    if not m:
+        return None, "summary holds no machine-readable traffic line"
+    if m.group(2) != schedule or abs(float(m.group(3)) - ratio) > 1e-9:
+        return None, "summary was taken with another schedule or ratio"
+    if m.group(4) != kernel_sources_sha16():
+        return None, "kernel sources changed since the --pmc runs (summary is stale)"
+    return float(m.group(1)), os.path.relpath(path, ROOT)
+
+
+def cpu_baseline(w, keep, full=False):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the workload:
+    one dense (first) layer on a sub-length of the request and one selective layer at the workload's
+    own row count against its full-length cache, at all cores and at one thread, with the L-layer
+    figure as a labelled linear extrapolation."""
     import numpy as np
     import torch
-    from threadpoolctl import threadpool_info
+    from threadpoolctl import threadpool_info, threadpool_limits
     from oracle import cacheblend_oracle as O
     from workloads import synth
     from dataclasses import replace
 
-    m2 = replace(w.model, n_layers=2)
-    rnd = O.storage_round(w.model.dtype)
-    layers = [{k: synth.to_f64(v) for k, v in synth.layer_weights(m2, l, w.seed_weights).items()}
-              for l in range(2)]
-    x = synth.to_f64(synth.hidden_inputs(w))
-    dt = synth.storage_dtype(w.model)
-    kpre = [synth.to_f64(synth.random_rows(w.n_ctx, m2.kv_dim, 0.5, 77 + l, dtype=dt)).reshape(
-        w.n_ctx, m2.n_kv_heads, m2.head_dim) for l in range(2)]
-    vpre = [synth.to_f64(synth.random_rows(w.n_ctx, m2.kv_dim, 0.5, 87 + l, dtype=dt)).reshape(
-        w.n_ctx, m2.n_kv_heads, m2.head_dim) for l in range(2)]
-    keep2 = [keep[0], keep[1] if len(keep) > 1 else keep[0]]
-    t0 = time.perf_counter()
-    out = O.fuse_prefill(x, layers, m2, w.chunk_lens, w.n_suffix, kpre, vpre, keep2, kv_round=rnd)
-    dt_s = time.perf_counter() - t0
+    m = w.model
+    rnd = O.storage_round(m.dtype)
+    C, S, T = w.n_ctx, w.n_suffix, w.n_tokens
+    if full:
+        layers = [{k: synth.to_f64(v) for k, v in lw.items()} for lw in synth.model_weights(m, w.seed_weights)]
+        x = synth.to_f64(synth.hidden_inputs(w))
+        t0 = time.perf_counter()
+        kpre, vpre = O.chunk_prefill(x[:C], w.chunk_lens, layers, m, rnd)
+        t1 = time.perf_counter()
+        out = O.fuse_prefill(x, layers, m, w.chunk_lens, S, kpre, vpre, keep, kv_round=rnd)
+        t2 = time.perf_counter()
+        sel_rows = sum(out.rows[1:])
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return {"value": sel_rows / max(t2 - t1, 1e-9), "unit": "token-layers/s", "cores": int(threads),
+                "kind": "oracle", "sample": f"the whole workload: chunk prefill {t1 - t0:.1f} s (setup), fusing pass "
+                f"{t2 - t1:.1f} s (layer 0 included in the time, not in the rows), numpy float64"}
+
+    lw = {k: synth.to_f64(v) for k, v in synth.layer_weights(m, 1, w.seed_weights).items()}
+    dt = synth.storage_dtype(m)
+    kc = synth.to_f64(synth.random_rows(T, m.kv_dim, 0.5, 77, dtype=dt)).reshape(T, m.n_kv_heads, m.head_dim)
+    vc = synth.to_f64(synth.random_rows(T, m.kv_dim, 0.5, 87, dtype=dt)).reshape(T, m.n_kv_heads, m.head_dim)
+    rows_sel = (keep[1] if len(keep) > 1 else keep[0]) + S          # rows entering the second selective layer
+    k_sel = (keep[2] if len(keep) > 2 else keep[-1])
+
+    def selective(n_rows, k_keep):
+        n_rows = min(n_rows, T)
+        k_keep = min(k_keep, n_rows - S)
+        pos = np.concatenate([np.sort(np.random.default_rng(5).choice(C, n_rows - S, replace=False)), np.arange(C, T)])
+        h = synth.to_f64(synth.random_rows(n_rows, m.d_model, 1.0, 97))
+        t0 = time.perf_counter()
+        O.fuse_layer(lw, m, h, pos, S, kc.copy(), vc.copy(), k_keep, kv_round=rnd)
+        return time.perf_counter() - t0, k_keep + S
+
+    def dense(n_rows):
+        h = synth.to_f64(synth.random_rows(n_rows, m.d_model, 1.0, 98))
+        t0 = time.perf_counter()
+        O.fuse_layer(lw, m, h, np.arange(n_rows), 0, kc[:n_rows].copy(), vc[:n_rows].copy(), n_rows, kv_round=rnd)
+        return time.perf_counter() - t0
+
+    # flops of a layer on r rows ~ 2 r P_l: size the samples to a few seconds each
+    p_l = m.params_per_layer
+    dense_rows = int(max(64, min(T, 2.0e12 / (2.0 * p_l))))
+    t_sel, kept_rows = selective(rows_sel, k_sel)
+    t_dense = dense(dense_rows)
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    rows = sum(out.rows)
-    return {"value": rows / dt_s, "unit": "token-layers/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"layers 0-1 of the workload at real width (full layer on {out.rows[0]} rows, then "
-                      f"K/V check on {out.rows[0]} rows and recompute of {out.rows[1]} rows), numpy float64, "
-                      f"{dt_s:.1f} s"}
+    one_rows = int(max(S + 8, min(rows_sel, 1.5e11 / (2.0 * p_l))))
+    with threadpool_limits(limits=1):
+        t_sel_1, kept_1 = selective(one_rows, max(0, one_rows - S - 4))
+    L = m.n_layers
+    sel_total = sum(k + S for k in keep[1:])
+    est = t_dense * T / dense_rows + t_sel / kept_rows * sel_total
+    return {"value": kept_rows / t_sel, "unit": "token-layers/s", "cores": int(threads), "kind": "oracle",
+            "seconds_selective_layer": t_sel, "seconds_dense_layer_sample": t_dense,
+            "one_thread_token_layers_per_s": kept_1 / t_sel_1,
+            "extrapolated_ttft_s": est,
+            "sample": f"one selective layer of the workload at real width ({rows_sel} rows in, {kept_rows} kept, "
+                      f"cache of {T} rows): {t_sel:.1f} s on {threads} threads; the same layer kind on {one_rows} rows "
+                      f"at 1 thread: {t_sel_1:.1f} s; one dense layer on the first {dense_rows} of {T} rows: "
+                      f"{t_dense:.1f} s; extrapolated_ttft_s = dense x {T}/{dense_rows} + selective per row x "
+                      f"{sel_total} rows of layers 1..{L - 1} (linear extrapolation, not a measurement); numpy float64"}
+
+
+def pct(values, q):
+    import numpy as np
+    return float(np.percentile(np.asarray(values, dtype=np.float64), q))
 
 
 def bench_batched(a, w, keep, P, producer, synth, torch, np):
@@ -143,24 +222,24 @@ def bench_batched(a, w, keep, P, producer, synth, torch, np):
         step()
         torch.cuda.synchronize()
         wall.append((time.perf_counter() - t0) * 1e3)
-    ms = float(np.mean(wall))
-    P.cb_profile_enable(ctx, True)
+    ms = float(np.median(wall))
+    P.cb_profile_enable(ctx, 1)
     restore()
     step()
     torch.cuda.synchronize()
     prof = P.cb_profile_read(ctx)
-    P.cb_profile_enable(ctx, False)
+    P.cb_profile_enable(ctx, 0)
     g = prof["gemm"]
     achieved = g["flops"] / g["ms"] / 1e9
-    token_layers = float(B * sum(k + S for k in keep))
+    token_layers = float(B * sum(k + S for k in keep[1:]))
     P.cb_destroy(ctx)
     print(json.dumps({
-        "metric": "hkvd_recompute_tokens_per_s (token-layers recomputed per second over one fused prefill)",
-        "value": token_layers / (ms * 1e-3), "unit": "token-layers/s", "n_gpus": 1, "steps": a.steps,
+        "metric": METRIC,
+        "value": token_layers / max(prof["phase_selective_layers"]["ms"] * 1e-3, 1e-12), "unit": "token-layers/s",
+        "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": ms, "ms_per_request": ms / B, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": m.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "batch": B, "layers": L, "n_ctx": C, "n_suffix": S, "ratio": w.ratio,
-                   "schedule": "flat" if a.flat else "gradual", "token_layers": token_layers},
+        "config": {"workload": w.name, "batch": B, "ratio": w.ratio, "schedule": "flat" if a.flat else "gradual"},
         "roofline": {"kernel": "gemm_bf16_dma_kernel (all epilogues)", "bound": "mfma", "achieved": achieved,
                      "peak": PEAK["mfma_bf16_tflops"], "unit": "TFLOP/s", "frac": achieved / PEAK["mfma_bf16_tflops"],
                      "traffic": None},
@@ -170,35 +249,29 @@ def bench_batched(a, w, keep, P, producer, synth, torch, np):
     }))
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path has no collectives); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def run_workload(a, name, ratio, steps, warmup, headline):
+    """Sets the workload up, times it, and returns its result dict (the headline's carries the
+    roofline object, the variants and the CPU baseline as well)."""
     import numpy as np
     import torch
-    from dataclasses import replace
     import paper_2405_16444_amd as P
     from paper_2405_16444_amd import producer
     from workloads import synth
     from workloads.configs import WORKLOADS
 
-    w = WORKLOADS[a.workload]
+    w = WORKLOADS[name]
     if a.layers:
         w = w.with_layers(a.layers)
-    if a.ratio is not None:
-        w = w.with_ratio(a.ratio)
+    if ratio is not None:
+        w = w.with_ratio(ratio)
     m = w.model
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
     L, C, S, T = m.n_layers, w.n_ctx, w.n_suffix, w.n_tokens
     keep = P.cb_default_schedule(L, C, w.ratio, w.ratio_first, a.flat)
-
-    if a.batch > 1:
-        return bench_batched(a, w, keep, P, producer, synth, torch, np)
+    schedule = "flat" if a.flat else "gradual"
 
     # ---- setup (untimed): weights, inputs, pre-computed chunk caches ----
+    t_setup = time.perf_counter()
     layers = [synth.layer_weights(m, l, w.seed_weights, device=dev) for l in range(L)]
     x = synth.hidden_inputs(w, device=dev)
     ctx = P.cb_create(m, T)
@@ -218,19 +291,24 @@ def main():
     sel_sets = [s.cpu().numpy() for s in out.sel]
     bench_out = None
     ws, structs = out.workspace, out.weight_structs
+    t_setup = time.perf_counter() - t_setup
 
     def step():
         nonlocal bench_out
         bench_out = P.cb_fuse_prefill(ctx, layers, x, w.chunk_lens, S, k_work, v_work, keep,
                                       workspace=ws, weight_structs=structs, out=bench_out)
 
-    for _ in range(a.warmup):
+    for _ in range(warmup):
         restore()
         step()
     torch.cuda.synchronize()
+    # timed steps: host clock around launch + completion; the library marks the end of layer 0 with
+    # an event (mode 2: three events per call, no per-launch brackets)
+    P.cb_profile_enable(ctx, 2)
+    P.cb_profile_read(ctx)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    gpu_ms, wall_ms = [], []
-    for _ in range(a.steps):
+    gpu_ms, wall_ms, first_ms, sel_ms = [], [], [], []
+    for _ in range(steps):
         restore()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -240,131 +318,216 @@ def main():
         torch.cuda.synchronize()
         wall_ms.append((time.perf_counter() - t0) * 1e3)
         gpu_ms.append(ev0.elapsed_time(ev1))
-    ms_per_step = float(np.sum(wall_ms) / a.steps)          # host clock around launch + completion
-    rows = [k + S for k in keep]
-    token_layers = float(sum(rows))
+        ph = P.cb_profile_read(ctx)
+        first_ms.append(ph["phase_first_layer"]["ms"])
+        sel_ms.append(ph["phase_selective_layers"]["ms"])
+    P.cb_profile_enable(ctx, 0)
+    ttft = float(np.median(wall_ms))
+    sel_rows = float(sum(k + S for k in keep[1:]))
+    sel_med = float(np.median(sel_ms))
+    res = {
+        "workload": w.name, "ratio": w.ratio, "schedule": schedule, "steps": steps, "warmup": warmup,
+        "ttft_ms": ttft, "ttft_ms_p10": pct(wall_ms, 10), "ttft_ms_p90": pct(wall_ms, 90),
+        "ttft_ms_mean": float(np.mean(wall_ms)), "ttft_ms_gpu_events_median": float(np.median(gpu_ms)),
+        "first_layer_ms": float(np.median(first_ms)), "selective_layers_ms": sel_med,
+        "selective_token_layers": sel_rows,
+        "hkvd_token_layers_per_s": sel_rows / max(sel_med * 1e-3, 1e-12),
+        "context_tokens_per_s": C / (ttft * 1e-3),
+        "rows_first_selective_layer": keep[1] + S if L > 1 else None, "rows_last_layer": keep[-1] + S,
+        "setup_s": t_setup,
+    }
 
     # ---- per-kernel-class times (HIP events around every launch, separate pass) ----
-    classes, roofline = {}, None
     if not a.no_profile:
-        P.cb_profile_enable(ctx, True)
-        n_prof = max(1, min(3, a.steps))
+        P.cb_profile_enable(ctx, 1)
+        n_prof = max(1, min(3, steps))
         for _ in range(n_prof):
             restore()
             step()
         torch.cuda.synchronize()
         prof = P.cb_profile_read(ctx)
-        P.cb_profile_enable(ctx, False)
+        P.cb_profile_enable(ctx, 0)
         prof["attention"]["flops"] = attention_flops(m, sel_sets, C, S) * n_prof
         es = 2 if m.dtype == "bf16" else 4
         prof["attention"]["bytes"] = 2.0 * T * m.kv_dim * es * L * n_prof   # K and V of a layer streamed once
+        classes = {}
         for c, v in prof.items():
-            if v["launches"]:
+            if v["launches"] and not c.startswith("phase_"):
+                tf = v["flops"] / v["ms"] / 1e9 if v["ms"] else 0.0
+                gb = v["bytes"] / v["ms"] / 1e6 if v["ms"] else 0.0
                 classes[c] = {"ms_per_step": v["ms"] / n_prof, "launches_per_step": v["launches"] // n_prof,
-                              "tflops": v["flops"] / v["ms"] / 1e9 if v["ms"] else 0.0,
-                              "gbs": v["bytes"] / v["ms"] / 1e6 if v["ms"] else 0.0}
+                              "tflops": tf, "frac_mfma_peak": tf / PEAK["mfma_bf16_tflops"],
+                              "gbs": gb, "frac_hbm_peak": gb / PEAK["hbm_gbs"]}
+        res["kernel_classes"] = classes
+        res["launches_per_step"] = sum(v["launches_per_step"] for v in classes.values())
         g = prof["gemm"]
         achieved = g["flops"] / g["ms"] / 1e9
-        roofline = {"kernel": "gemm_bf16_dma_kernel (all epilogues)", "bound": "mfma", "achieved": achieved,
-                    "peak": PEAK["mfma_bf16_tflops"], "unit": "TFLOP/s", "frac": achieved / PEAK["mfma_bf16_tflops"],
-                    "traffic": PMC_TRAFFIC_BYTES_PER_GEMM_LAUNCH.get(
-                        (w.name, "flat" if a.flat else "gradual", L, w.ratio)),
-                    "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 --pmc)",
-                    "algorithmic_bytes_per_launch": g["bytes"] / g["launches"],
-                    "avg_launch_us": g["ms"] / g["launches"] * 1e3,
-                    "flops_per_launch": g["flops"] / g["launches"]}
+        traffic, traffic_src = pmc_traffic(w.name, schedule, w.ratio) if not a.layers else (None, "reduced depth")
+        res["roofline"] = {"kernel": "gemm_bf16_dma_kernel (all epilogues)", "bound": "mfma", "achieved": achieved,
+                           "peak": PEAK["mfma_bf16_tflops"], "unit": "TFLOP/s",
+                           "frac": achieved / PEAK["mfma_bf16_tflops"],
+                           "traffic": traffic, "traffic_source": traffic_src,
+                           "traffic_unit": "bytes per launch (L2 <-> fabric, rocprofv3 --pmc)",
+                           "algorithmic_bytes_per_launch": g["bytes"] / g["launches"],
+                           "avg_launch_us": g["ms"] / g["launches"] * 1e3,
+                           "flops_per_launch": g["flops"] / g["launches"]}
 
-    # ---- the same call recorded once into a HIP graph and replayed (not part of `value`: a graph
-    # serves requests of one chunk structure and schedule only) ----
-    graph_replay = None
-    if not a.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        restore()
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph):
-            step()
-        torch.cuda.synchronize()
-        g_ms = []
-        for i in range(2 + min(a.steps, 5)):
+    if headline:
+        # ---- the same call recorded once into a HIP graph and replayed (not part of `value`: a graph
+        # serves requests of one chunk structure and schedule only) ----
+        if not a.no_graph:
+            graph = torch.cuda.CUDAGraph()
             restore()
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            graph.replay()
+            with torch.cuda.graph(graph):
+                step()
             torch.cuda.synchronize()
-            if i >= 2:
-                g_ms.append((time.perf_counter() - t0) * 1e3)
-        graph_replay = {"ttft_ms": float(np.mean(g_ms)), "steps": len(g_ms)}
-        del graph
+            g_ms = []
+            for i in range(2 + min(steps, 5)):
+                restore()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                if i >= 2:
+                    g_ms.append((time.perf_counter() - t0) * 1e3)
+            res["graph_replay"] = {"ttft_ms": float(np.median(g_ms)), "steps": len(g_ms)}
+            del graph
 
-    # ---- first-token head on the prefill's final hidden states (not part of `value`) ----
-    head = synth.head_weights(m, w.seed_weights, device=dev)
-    logits, token = P.cb_first_token(ctx, bench_out.final_hidden, head["final_norm"], head["lm_head"])
+        # ---- first-token head on the prefill's final hidden states (not part of `value`) ----
+        head = synth.head_weights(m, w.seed_weights, device=dev)
+        logits, token = P.cb_first_token(ctx, bench_out.final_hidden, head["final_norm"], head["lm_head"])
+        torch.cuda.synchronize()
+        n_head = 20
+        ev0.record()
+        for _ in range(n_head):
+            P.cb_first_token(ctx, bench_out.final_hidden, head["final_norm"], head["lm_head"], logits=logits, token=token)
+        ev1.record()
+        torch.cuda.synchronize()
+        head_ms = ev0.elapsed_time(ev1) / n_head
+        head_bytes = m.vocab * m.d_model * (2 if m.dtype == "bf16" else 4)
+        res["first_token"] = {"ms": head_ms, "vocab": m.vocab, "gbs": head_bytes / head_ms / 1e6,
+                              "frac_hbm": head_bytes / head_ms / 1e6 / PEAK["hbm_gbs"],
+                              "ttft_with_first_token_ms": ttft + head_ms,
+                              "note": "weights stay in the memory-side cache between repeats when they fit"}
+        del head
+
+        # ---- same pass with the chunk caches in pinned host memory, loaded layer by layer on a
+        # second stream while earlier layers compute (PCIe-inclusive; not part of `value`) ----
+        if not a.no_host_load:
+            k_host = [torch.empty(t[:C].shape, dtype=t.dtype, pin_memory=True).copy_(t[:C]) for t in k_pre]
+            v_host = [torch.empty(t[:C].shape, dtype=t.dtype, pin_memory=True).copy_(t[:C]) for t in v_pre]
+            copy_stream = torch.cuda.Stream()
+            pout = None
+            hl_ms = []
+            for i in range(2 + min(steps, 5)):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                pout = P.cb_fuse_prefill_pipelined(ctx, layers, x, w.chunk_lens, S, k_host, v_host, k_work, v_work,
+                                                   keep, copy_stream, workspace=ws, weight_structs=structs, out=pout)
+                torch.cuda.synchronize()
+                if i >= 2:
+                    hl_ms.append((time.perf_counter() - t0) * 1e3)
+            same = bool(torch.equal(pout.final_hidden, bench_out.final_hidden))
+            kv_bytes = sum(t.numel() * t.element_size() for t in k_host[1:] + v_host[1:])   # layer 0 is recomputed in full, not loaded
+            host_load = {"ttft_ms": float(np.median(hl_ms)), "kv_bytes_loaded": kv_bytes,
+                         "serial_copy_ms_at_rate_seen": None, "equals_resident_result": same}
+            # plain copy of the same bytes alone, for the PCIe rate of this machine
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for dst, src in zip(k_work[1:] + v_work[1:], k_host[1:] + v_host[1:]):
+                dst[:C].copy_(src, non_blocking=True)
+            torch.cuda.synchronize()
+            copy_ms = (time.perf_counter() - t0) * 1e3
+            host_load["serial_copy_ms_at_rate_seen"] = copy_ms
+            host_load["h2d_gbs"] = kv_bytes / copy_ms / 1e6
+            res["host_load"] = host_load
+            del k_host, v_host
+
+    P.cb_destroy(ctx)
+    res["_keep"] = keep
+    res["_workload"] = w
+    del layers, x, k_pre, v_pre, k_work, v_work, out, bench_out, ws
+    torch.cuda.empty_cache()
+    return res
+
+
+def copy_ceiling_gbs():
+    """Plain device-to-device copy of 1 GiB (read + write counted): the streaming rate this machine reaches."""
+    import torch
+    x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    y = torch.empty_like(x)
+    for _ in range(3):
+        y.copy_(x)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
-    n_head = 20
     ev0.record()
-    for _ in range(n_head):
-        P.cb_first_token(ctx, bench_out.final_hidden, head["final_norm"], head["lm_head"], logits=logits, token=token)
+    for _ in range(10):
+        y.copy_(x)
     ev1.record()
     torch.cuda.synchronize()
-    head_ms = ev0.elapsed_time(ev1) / n_head
-    head_bytes = m.vocab * m.d_model * (2 if m.dtype == "bf16" else 4)
-    first_token = {"ms": head_ms, "vocab": m.vocab, "gbs": head_bytes / head_ms / 1e6,
-                   "frac_hbm": head_bytes / head_ms / 1e6 / PEAK["hbm_gbs"],
-                   "ttft_with_first_token_ms": ms_per_step + head_ms,
-                   "note": "weights stay in the memory-side cache between repeats when they fit"}
+    ms = ev0.elapsed_time(ev1) / 10
+    del x, y
+    torch.cuda.empty_cache()
+    return 2.0 * (1 << 30) / ms / 1e6
 
-    # ---- same pass with the chunk caches in pinned host memory, loaded layer by layer on a
-    # second stream while earlier layers compute (PCIe-inclusive; not part of `value`) ----
-    host_load = None
-    if not a.no_host_load:
-        k_host = [torch.empty(t[:C].shape, dtype=t.dtype, pin_memory=True).copy_(t[:C]) for t in k_pre]
-        v_host = [torch.empty(t[:C].shape, dtype=t.dtype, pin_memory=True).copy_(t[:C]) for t in v_pre]
-        copy_stream = torch.cuda.Stream()
-        pout = None
-        hl_ms = []
-        for i in range(2 + min(a.steps, 5)):
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            pout = P.cb_fuse_prefill_pipelined(ctx, layers, x, w.chunk_lens, S, k_host, v_host, k_work, v_work,
-                                               keep, copy_stream, workspace=ws, weight_structs=structs, out=pout)
-            torch.cuda.synchronize()
-            if i >= 2:
-                hl_ms.append((time.perf_counter() - t0) * 1e3)
-        same = bool(torch.equal(pout.final_hidden, bench_out.final_hidden))
-        kv_bytes = sum(t.numel() * t.element_size() for t in k_host[1:] + v_host[1:])   # layer 0 is recomputed in full, not loaded
-        host_load = {"ttft_ms": float(np.mean(hl_ms)), "kv_bytes_loaded": kv_bytes,
-                     "serial_copy_ms_at_rate_seen": None, "equals_resident_result": same}
-        # plain copy of the same bytes alone, for the PCIe rate of this machine
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for dst, src in zip(k_work[1:] + v_work[1:], k_host[1:] + v_host[1:]):
-            dst[:C].copy_(src, non_blocking=True)
-        torch.cuda.synchronize()
-        copy_ms = (time.perf_counter() - t0) * 1e3
-        host_load["serial_copy_ms_at_rate_seen"] = copy_ms
-        host_load["h2d_gbs"] = kv_bytes / copy_ms / 1e6
-        del k_host, v_host
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2405_16444_amd as P
+    from paper_2405_16444_amd import producer
+    from workloads import synth
+    from workloads.configs import WORKLOADS
+
+    torch.cuda.set_device(0)
+    if a.batch > 1:
+        w = WORKLOADS[a.workload]
+        if a.layers:
+            w = w.with_layers(a.layers)
+        if a.ratio is not None:
+            w = w.with_ratio(a.ratio)
+        keep = P.cb_default_schedule(w.model.n_layers, w.n_ctx, w.ratio, w.ratio_first, a.flat)
+        return bench_batched(a, w, keep, P, producer, synth, torch, np)
+
+    head = run_workload(a, a.workload, a.ratio, a.steps, a.warmup, headline=True)
+    keep, w = head.pop("_keep"), head.pop("_workload")
+    extras = []
+    if not a.no_extra and not a.layers:
+        for name, ratio in EXTRA:
+            if name == a.workload and ratio in (None, a.ratio, w.ratio):
+                continue
+            r = run_workload(a, name, ratio, max(1, min(a.steps, 5)), max(1, min(a.warmup, 2)), headline=False)
+            r.pop("_keep")
+            r.pop("_workload")
+            extras.append(r)
 
     cpu = None
     if not a.no_cpu_baseline:
-        cpu = cpu_baseline(w, keep)
+        cpu = cpu_baseline(w, keep, full=a.full_oracle)
 
-    P.cb_destroy(ctx)
     res = {
-        "metric": "hkvd_recompute_tokens_per_s (token-layers recomputed per second over one fused prefill)",
-        "value": token_layers / (ms_per_step * 1e-3), "unit": "token-layers/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
-        "ttft_ms": ms_per_step, "ttft_ms_gpu_events_median": float(np.median(gpu_ms)),
-        "context_tokens_per_s": C / (ms_per_step * 1e-3),
+        "metric": METRIC,
+        "value": head["hkvd_token_layers_per_s"], "unit": "token-layers/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": head["ttft_ms"],
+        "ttft_ms": head["ttft_ms"], "ttft_ms_p10": head["ttft_ms_p10"], "ttft_ms_p90": head["ttft_ms_p90"],
+        "ttft_ms_mean": head["ttft_ms_mean"], "ttft_ms_gpu_events_median": head["ttft_ms_gpu_events_median"],
+        "first_layer_ms": head["first_layer_ms"], "selective_layers_ms": head["selective_layers_ms"],
+        "selective_token_layers": head["selective_token_layers"],
+        "context_tokens_per_s": head["context_tokens_per_s"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": m.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "layers": L, "d_model": m.d_model, "heads": f"{m.n_q_heads}/{m.n_kv_heads}x{m.head_dim}",
-                   "d_ff": m.d_ff, "chunks": f"{len(w.chunk_lens)}x{w.chunk_lens[0]}" if len(set(w.chunk_lens)) == 1
-                   else f"{len(w.chunk_lens)} ragged", "n_ctx": C, "n_suffix": S, "ratio": w.ratio,
-                   "schedule": "flat" if a.flat else "gradual", "keep_first": keep[1] if L > 1 else C,
-                   "keep_last": keep[-1], "token_layers": token_layers},
-        "roofline": roofline, "cpu_baseline": cpu, "kernel_classes": classes, "first_token": first_token,
-        "host_load": host_load, "graph_replay": graph_replay,
+        "dtype": w.model.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "ratio": w.ratio, "schedule": head["schedule"]},
+        "roofline": head.get("roofline"), "cpu_baseline": cpu,
+        "hbm_copy_ceiling_gbs": copy_ceiling_gbs(),
+        "kernel_classes": head.get("kernel_classes"), "launches_per_step": head.get("launches_per_step"),
+        "first_token": head.get("first_token"), "host_load": head.get("host_load"),
+        "graph_replay": head.get("graph_replay"), "workloads": extras,
     }
     print(json.dumps(res))
 

@@ -252,12 +252,19 @@ double cb_pick_recompute_ratio(double prefill_delay, double load_delay, double m
 int32_t cb_pick_storage_device(double recompute_delay, const double *load_delays, const double *costs,
                                int32_t n);
 
-/* Per-kernel-class timing for benchmarks.  Classes: */
+/* Instrumentation for benchmarks (no operation of the paper): HIP-event timing per kernel class.
+ * Classes: projections' main launches; attention (+ merge of key-range pieces); re-alignment; the K/V
+ * projection's finish launch that also computes the deviation; selection + cache update; stand-alone
+ * RMSNorm; copies and conversions; the other finish launches (sum of parked sums + residual + norm, SwiGLU
+ * tail); first-token head; and two PHASES of cb_fuse_prefill / cb_fuse_prefill_pipelined that span many
+ * launches: everything up to the end of layer 0 (input conversion, re-alignment, the full first layer), and
+ * the selective layers 1 .. L-1 with the final copy. */
 enum { CB_PROF_GEMM = 0, CB_PROF_ATTN = 1, CB_PROF_REALIGN = 2, CB_PROF_DEV = 3,
        CB_PROF_TOPK = 4, CB_PROF_NORM = 5, CB_PROF_OTHER = 6, CB_PROF_REDUCE = 7,
-       CB_PROF_HEAD = 8, CB_PROF_NCLASS = 9 };
-/* enable != 0: every later launch on ctx is bracketed by a pair of HIP events on
- * its stream (this slows the pass a little; do not time whole calls meanwhile). */
+       CB_PROF_HEAD = 8, CB_PROF_PHASE_FIRST = 9, CB_PROF_PHASE_SELECTIVE = 10, CB_PROF_NCLASS = 11 };
+/* enable = 1: every later launch on ctx is bracketed by a pair of HIP events on its stream (this
+ * slows the pass a little; do not time whole calls meanwhile).  enable = 2: only the two phases are
+ * bracketed (three events per call: whole-call timing stays valid).  enable = 0: off. */
 int cb_profile_enable(cb_ctx *ctx, int32_t enable);
 /* Synchronises the events recorded since the last read, adds up milliseconds,
  * launch counts, algorithmic flops and algorithmic bytes per class into HOST

@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libcachebl
 
 CB_F32, CB_BF16 = 0, 1
 PROF_CLASSES = ("gemm", "attention", "realign", "deviation", "topk", "norm", "other", "finish",
-                "first_token")
+                "first_token", "phase_first_layer", "phase_selective_layers")
 
 
 class CacheBlendError(RuntimeError):
@@ -433,7 +433,8 @@ def cb_pick_storage_device(recompute_delay: float, load_delays: Sequence[float],
     return _lib.cb_pick_storage_device(recompute_delay, (C.c_double * n)(*load_delays), (C.c_double * n)(*costs), n)
 
 
-def cb_profile_enable(ctx: Context, enable: bool):
+def cb_profile_enable(ctx: Context, enable):
+    """0 / False: off; 1 / True: every launch and the two phases; 2: the two phases only."""
     _check(_lib.cb_profile_enable(ctx._h, int(enable)), "cb_profile_enable")
 
 

@@ -32,7 +32,7 @@ struct cb_ctx {
   int max_tokens;
   int device;
   float2 *rope_tab;  // device [max_tokens][head_dim/2]
-  bool profiling;
+  int profiling;                         // 0 off, 1 every launch and the two phases, 2 the two phases only
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> free_events;
   std::vector<hipEvent_t> load_events;   // pipelined loading: [0] = entry fence, [1 + l] = layer l landed
@@ -84,7 +84,8 @@ struct ProfScope {
   ProfRec r;
   bool on;
   ProfScope(cb_ctx *ctx, hipStream_t st, int cls, double flops, double bytes) : c(ctx), s(st) {
-    on = ctx->profiling;
+    // the phase classes span many launches and are recorded in both modes
+    on = ctx->profiling == 1 || (ctx->profiling == 2 && cls >= CB_PROF_PHASE_FIRST);
     if (!on) return;
     r.cls = cls; r.flops = flops; r.bytes = bytes;
     r.start = take_event(c);
@@ -401,7 +402,7 @@ int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out) {
   if (!c) return CB_ENOMEM;
   c->m = m;
   c->max_tokens = max_tokens;
-  c->profiling = false;
+  c->profiling = 0;
   c->rope_tab = nullptr;
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return CB_EHIP; }
   c->static_scratch = static_scratch_of(c->device);
@@ -532,8 +533,8 @@ int cb_fuse_layer_static(cb_ctx *c, int32_t layer, const cb_layer_weights *w, co
   if (hipGetDevice(&device) != hipSuccess) return CB_EHIP;
   if (device != c->device) return CB_EINVAL;   // the ctx's device holds the scratch this call would use
   // per-launch timing creates events; this entry point creates nothing
-  const bool profiling = c->profiling;
-  c->profiling = false;
+  const int profiling = c->profiling;
+  c->profiling = 0;
   const int st = cb_fuse_layer(c, layer, w, h_in, row_pos, n_rows, n_suffix, k_cache, v_cache, n_tokens_total,
                                k_keep, forced_sel, h_out, pos_out, dev_out, c->static_scratch,
                                CB_STATIC_SCRATCH_BYTES, stream);
@@ -614,6 +615,9 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
   int32_t *p_cur = (int32_t *)(base + 2 * hb), *p_nxt = (int32_t *)(base + 2 * hb + pb);
   LayerWs ws = carve_layer(c, base + 2 * hb + 2 * pb, T);
 
+  // phase marks: everything up to the end of layer 0 (the full first layer), then the selective layers
+  ProfScope *phase = new (std::nothrow) ProfScope(c, s, CB_PROF_PHASE_FIRST, 0, 0);
+  struct PhaseGuard { ProfScope *&p; ~PhaseGuard() { delete p; } } phase_guard{phase};
   {
     ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)T * d * (4 + esize(c)));
     CB_HIP(launch_to_f32(c->m.dtype, x, h_cur, (size_t)T * d, s));
@@ -652,6 +656,10 @@ int prefill_impl(cb_ctx *c, const cb_layer_weights *layers, const void *x, const
     std::swap(h_cur, h_nxt);
     std::swap(p_cur, p_nxt);
     n = k + n_suffix;
+    if (l == 0) {
+      delete phase;
+      phase = L > 1 ? new (std::nothrow) ProfScope(c, s, CB_PROF_PHASE_SELECTIVE, 0, 0) : nullptr;
+    }
   }
   if (n_suffix > 0) {
     ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)n_suffix * d * 8);
@@ -862,7 +870,8 @@ int32_t cb_pick_storage_device(double recompute_delay, const double *load_delays
 
 int cb_profile_enable(cb_ctx *c, int32_t enable) {
   if (!c) return CB_ENULL;
-  c->profiling = enable != 0;
+  if (enable < 0 || enable > 2) return CB_EINVAL;
+  c->profiling = enable;
   return CB_OK;
 }
 

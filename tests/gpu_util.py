@@ -31,6 +31,22 @@ def max_abs_rel(got, ref) -> float:
     return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
 
 
+def dev_noise_bound(k_rows, v_rows, dtype: str):
+    """Largest deviation a candidate can show when its exact new K/V EQUAL its cached K/V (a token of
+    the first chunk: a prefix, so its exact deviation is zero).  Two things separate the stored new row
+    from its cached twin: (a) the hidden state it is projected from, which on this path matches the exact
+    one only within the parity tolerance tol (relative), and the projection is linear in it; (b) the
+    storage rounding of both rows, at most one unit in the last place per element, 2^-p |x| with p = 7
+    for bf16 (8-bit significand, the coarsest spacing of a binade) and 23 for float.  Element-wise
+    |new - cached| <= (tol + 2^-p) |x| in the norm of the row, hence
+        dev <= (tol + 2^-p)^2 (|K row|^2 + |V row|^2).
+    k_rows, v_rows: the candidates' cached rows [n, Hkv, dh] (the norm does not depend on the rotation)."""
+    p = 7 if dtype == "bf16" else 23
+    k = np.asarray(k_rows, np.float64).reshape(len(k_rows), -1)
+    v = np.asarray(v_rows, np.float64).reshape(len(v_rows), -1)
+    return (TOL[dtype] + 2.0 ** -p) ** 2 * ((k * k).sum(axis=1) + (v * v).sum(axis=1))
+
+
 def to_np(t: torch.Tensor):
     return t.detach().to("cpu").to(torch.float64).numpy()
 

@@ -13,8 +13,8 @@ from oracle import cacheblend_oracle as O
 from workloads import synth
 from workloads.configs import ModelShape, Workload, WORKLOADS
 
-from gpu_util import (TOL, announce, cache_tensors, dev_layers, max_abs_rel, np_layers, oracle_caches,
-                      scaled_weights, to_np)
+from gpu_util import (TOL, announce, cache_tensors, dev_layers, dev_noise_bound, max_abs_rel, np_layers,
+                      oracle_caches, scaled_weights, to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -229,8 +229,11 @@ def check_prefill_against_oracle(w, npl, xn, kpre, vpre, keep, out, kg, vg, tol)
         if keep[l] < (w.n_ctx if l == 0 else keep[l - 1]):
             got = out.dev[l].cpu().numpy()
             if ref.dev[l].size and ref.dev[l].max() < 1e-9:
-                # every candidate sits in the first chunk (a prefix): the deviation is rounding noise
-                assert got.max() < (1e-6 if w.model.dtype == "f32" else 0.5), f"dev layer {l}"
+                # every candidate sits in the first chunk (a prefix): its exact deviation is zero and what
+                # the GPU reports is storage-rounding noise, bounded per candidate by dev_noise_bound
+                cand_l = np.arange(w.n_ctx) if l == 0 else sel_gpu[l - 1]
+                bound = dev_noise_bound(kpre[l][cand_l], vpre[l][cand_l], w.model.dtype)
+                assert np.all(got <= bound), f"dev layer {l}: {got.max()} vs {bound.max()}"
             else:
                 assert max_abs_rel(got, ref.dev[l]) < tol, f"dev layer {l}"
         assert max_abs_rel(to_np(kg[l].cpu()), ref.K[l]) < tol, f"K layer {l}"
