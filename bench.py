@@ -31,8 +31,10 @@ sys.path.insert(0, ROOT)
 PEAK = {"mfma_bf16_tflops": 2500.0, "hbm_gbs": 8000.0}
 METRIC = "hkvd_recompute_tokens_per_s (token-layers recomputed per second on the selective layers of one fused prefill)"
 # (workload, ratio or None = the workload's own) measured after the headline, fewer steps each
-EXTRA = [("mistral7b", None), ("yi34b", 0.05), ("yi34b", 0.15), ("yi34b", 0.30), ("long32k", None),
-         ("long_ragged", None)]
+EXTRA = [("mistral7b", None, False), ("yi34b", 0.05, False), ("yi34b", 0.15, False), ("yi34b", 0.30, False),
+         ("long32k", None, False), ("long_ragged", None, False),
+         # 8-bit projection weights (the paper serves its two larger models 8-bit, Sec. 7.1)
+         ("yi34b", 0.15, True), ("llama70b", None, True)]
 
 
 def parse():
@@ -50,6 +52,7 @@ def parse():
                          "seconds for `tiny`, tens of minutes for the Mistral-7B shape")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="headline workload only")
+    ap.add_argument("--int8", action="store_true", help="headline workload with 8-bit projection weights")
     ap.add_argument("--batch", type=int, default=1,
                     help="requests fused per call (cb_fuse_prefill_batched when > 1; distinct inputs per request)")
     ap.add_argument("--no-host-load", action="store_true",
@@ -249,7 +252,7 @@ def bench_batched(a, w, keep, P, producer, synth, torch, np):
     }))
 
 
-def run_workload(a, name, ratio, steps, warmup, headline):
+def run_workload(a, name, ratio, steps, warmup, headline, int8=False):
     """Sets the workload up, times it, and returns its result dict (the headline's carries the
     roofline object, the variants and the CPU baseline as well)."""
     import numpy as np
@@ -264,6 +267,9 @@ def run_workload(a, name, ratio, steps, warmup, headline):
         w = w.with_layers(a.layers)
     if ratio is not None:
         w = w.with_ratio(ratio)
+    if int8:
+        from dataclasses import replace
+        w = replace(w, name=w.name + "-int8", model=replace(w.model, weight_format="int8"))
     m = w.model
     dev = torch.device("cuda:0")
     L, C, S, T = m.n_layers, w.n_ctx, w.n_suffix, w.n_tokens
@@ -272,7 +278,8 @@ def run_workload(a, name, ratio, steps, warmup, headline):
 
     # ---- setup (untimed): weights, inputs, pre-computed chunk caches ----
     t_setup = time.perf_counter()
-    layers = [synth.layer_weights(m, l, w.seed_weights, device=dev) for l in range(L)]
+    layers = [synth.layer_weights(m, l, w.seed_weights, device=dev) for l in range(L)] if not int8 else \
+             [synth.quantize_int8(synth.layer_weights(m, l, w.seed_weights, device=dev)) for l in range(L)]
     x = synth.hidden_inputs(w, device=dev)
     ctx = P.cb_create(m, T)
     k_pre, v_pre = producer.chunk_prefill(ctx, layers, x[:C], w.chunk_lens, T)
@@ -495,14 +502,15 @@ def main():
         keep = P.cb_default_schedule(w.model.n_layers, w.n_ctx, w.ratio, w.ratio_first, a.flat)
         return bench_batched(a, w, keep, P, producer, synth, torch, np)
 
-    head = run_workload(a, a.workload, a.ratio, a.steps, a.warmup, headline=True)
+    head = run_workload(a, a.workload, a.ratio, a.steps, a.warmup, headline=True, int8=a.int8)
     keep, w = head.pop("_keep"), head.pop("_workload")
     extras = []
     if not a.no_extra and not a.layers:
-        for name, ratio in EXTRA:
-            if name == a.workload and ratio in (None, a.ratio, w.ratio):
+        for name, ratio, int8 in EXTRA:
+            if name == a.workload and ratio in (None, a.ratio, w.ratio) and not int8:
                 continue
-            r = run_workload(a, name, ratio, max(1, min(a.steps, 5)), max(1, min(a.warmup, 2)), headline=False)
+            r = run_workload(a, name, ratio, max(1, min(a.steps, 5)), max(1, min(a.warmup, 2)), headline=False,
+                             int8=int8)
             r.pop("_keep")
             r.pop("_workload")
             extras.append(r)

@@ -58,16 +58,29 @@ typedef enum { CB_F32 = 0, CB_BF16 = 1 } cb_dtype;
  * channels renumbered; the caches a caller hands in must be in the same order. */
 typedef enum { CB_ROPE_ADJACENT = 0, CB_ROPE_HALF = 1 } cb_rope_layout;
 
+/* How the seven projection matrices of a layer are stored (Sec. 7.1 serves its two larger models
+ * with 8-bit weights; the paper names no scheme, this is weight-only symmetric int8):
+ *   CB_W_NATIVE  elements of storage type T
+ *   CB_W_INT8    int8 elements q with one float scale per OUTPUT feature (row of the [out, in]
+ *                matrix): w[o][i] = q[o][i] * scale[o].  Needs dtype == CB_BF16.  Arithmetic stays
+ *                bf16 x bf16 -> float on the matrix cores: a projection's weights are expanded to
+ *                bf16 (rounded to nearest even) into the workspace right before it runs, so HBM holds
+ *                one byte per weight and the workspace one projection's worth of bf16.
+ * Norm gains, the final norm and the vocabulary matrix of cb_first_token are always of type T. */
+typedef enum { CB_W_NATIVE = 0, CB_W_INT8 = 1 } cb_weight_format;
+
 /* Decoder geometry (RMSNorm, grouped-query attention, rotary embedding as in
  * Appendix A, SwiGLU MLP, no biases). */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
   float rms_eps, rope_theta;
-  int32_t dtype;       /* cb_dtype */
-  int32_t rope_layout; /* cb_rope_layout */
+  int32_t dtype;         /* cb_dtype */
+  int32_t rope_layout;   /* cb_rope_layout */
+  int32_t weight_format; /* cb_weight_format */
 } cb_model_desc;
 
-/* One layer's weights (all of storage type T). */
+/* One layer's weights: norm gains of storage type T; matrices of T, or int8 with the scale arrays
+ * below when weight_format == CB_W_INT8 (the scale pointers are ignored otherwise). */
 typedef struct {
   const void *attn_norm;      /* [d_model] */
   const void *wq, *wk, *wv;   /* [Hq*dh, d], [Hkv*dh, d], [Hkv*dh, d] */
@@ -75,6 +88,11 @@ typedef struct {
   const void *mlp_norm;       /* [d_model] */
   const void *w_gate, *w_up;  /* [d_ff, d] */
   const void *w_down;         /* [d, d_ff] */
+  /* CB_W_INT8: float scale per output feature of the matrix of the same name */
+  const float *wq_scale, *wk_scale, *wv_scale;   /* [Hq*dh], [Hkv*dh], [Hkv*dh] */
+  const float *wo_scale;                         /* [d] */
+  const float *w_gate_scale, *w_up_scale;        /* [d_ff] */
+  const float *w_down_scale;                     /* [d] */
 } cb_layer_weights;
 
 typedef struct cb_ctx cb_ctx;

@@ -69,6 +69,23 @@ def round_bf16(a):
     return u.astype(np.uint32).view(np.float32).astype(F64).reshape(f.shape)
 
 
+def dequantize_int8(lw):
+    """Layer weights stored 8-bit (the paper serves its two larger models with 8-bit weights, Sec. 7.1,
+    without naming a scheme; this build's reading is weight-only symmetric int8 with one scale per output
+    feature -- "parity unpinned" by the paper): every matrix name that comes with a `<name>_scale` vector
+    means w[o, i] = q[o, i] * scale[o].  Returns the layer with those matrices in float64; everything
+    downstream is the ordinary definition of the block."""
+    out = {}
+    for name, v in lw.items():
+        if name.endswith("_scale"):
+            continue
+        if name + "_scale" in lw:
+            out[name] = np.asarray(v, F64) * np.asarray(lw[name + "_scale"], F64)[:, None]
+        else:
+            out[name] = np.asarray(v, F64)
+    return out
+
+
 def storage_round(dtype: str):
     return {"f32": identity, "bf16": round_bf16}[dtype]
 

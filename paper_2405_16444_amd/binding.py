@@ -28,17 +28,20 @@ class _ModelDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32),
-                ("rope_layout", C.c_int32)]
+                ("rope_layout", C.c_int32), ("weight_format", C.c_int32)]
 
 
 _ROPE_LAYOUTS = {"adjacent": 0, "half": 1}
+_WEIGHT_FORMATS = {"native": 0, "int8": 1}
 
 
 _WEIGHT_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate", "w_up", "w_down")
+_MATRIX_FIELDS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+_SCALE_FIELDS = tuple(n + "_scale" for n in _MATRIX_FIELDS)
 
 
 class _LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS + _SCALE_FIELDS]
 
 
 def _load():
@@ -124,10 +127,18 @@ def _torch_dtype(code: int):
 
 
 def _weights_struct(lw: Dict[str, torch.Tensor], dtype, device) -> _LayerWeights:
+    """Pointers of one layer.  Matrices are of `dtype`, or int8 with a float `<name>_scale` vector each."""
     s = _LayerWeights()
     for name in _WEIGHT_FIELDS:
         t = lw[name]
-        assert t.dtype == dtype and t.is_contiguous() and t.device == device, name
+        assert t.is_contiguous() and t.device == device, name
+        if t.dtype == torch.int8:
+            sc = lw[name + "_scale"]
+            assert name in _MATRIX_FIELDS and sc.dtype == torch.float32 and sc.is_contiguous(), name
+            assert sc.device == device and sc.numel() == t.shape[0], name
+            setattr(s, name + "_scale", sc.data_ptr())
+        else:
+            assert t.dtype == dtype, name
         setattr(s, name, t.data_ptr())
     return s
 
@@ -150,7 +161,9 @@ class Context:
         self.dtype = _torch_dtype(self.dtype_code)
         desc = _ModelDesc(model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads,
                           model.head_dim, model.d_ff, model.rms_eps, model.rope_theta, self.dtype_code,
-                          _ROPE_LAYOUTS[getattr(model, "rope_layout", "adjacent")])
+                          _ROPE_LAYOUTS[getattr(model, "rope_layout", "adjacent")],
+                          _WEIGHT_FORMATS[getattr(model, "weight_format", "native")])
+        self.int8_weights = getattr(model, "weight_format", "native") == "int8"
         handle = C.c_void_p()
         _check(_lib.cb_create(C.byref(desc), self.max_tokens, C.byref(handle)), "cb_create")
         self._h = handle

@@ -101,6 +101,7 @@ struct ProfScope {
 
 struct LayerWs {
   void *xn, *xn2, *kvnew, *qbuf, *obuf, *act;
+  void *wstage;          // int8 weights: bf16 expansion of the projection that runs next
   float *hmid, *partial, *dev;
   int32_t *sel_rows;
   size_t partial_floats;
@@ -161,6 +162,10 @@ LayerWs carve_layer(const cb_ctx *c, char *base, int R) {
   w.partial = (float *)take(w.partial_floats * 4);
   w.dev = (float *)take((size_t)R * 4);
   w.sel_rows = (int32_t *)take((size_t)R * 4);
+  // the widest projection (gate and up together, or Q, K and V together) expanded to bf16
+  const size_t stage = m.weight_format == CB_W_INT8
+                           ? std::max((size_t)2 * m.d_ff, q_dim + 2 * kv_dim) * m.d_model * 2 : 0;
+  w.wstage = take(stage);
   w.bytes = off;
   return w;
 }
@@ -186,6 +191,18 @@ bool weights_aligned(const cb_layer_weights *w) {
          aligned(w->w_down, 16);
 }
 
+// int8 weights: every matrix needs its scale array (float, 4-byte aligned)
+int scales_ok_status(const cb_layer_weights *w) {
+  const float *sc[7] = {w->wq_scale, w->wk_scale, w->wv_scale, w->wo_scale, w->w_gate_scale, w->w_up_scale,
+                        w->w_down_scale};
+  for (const float *p : sc) {
+    if (!p) return CB_ENULL;
+    if (!aligned(p, 4)) return CB_EINVAL;
+  }
+  return CB_OK;
+}
+bool scales_ok(const cb_layer_weights *w) { return scales_ok_status(w) == CB_OK; }
+
 int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int n_rows, int n_suffix,
                      int n_tokens_total, int k_keep) {
   if (!c || !w) return CB_ENULL;
@@ -193,10 +210,33 @@ int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int 
       !w->w_down)
     return CB_ENULL;
   if (!weights_aligned(w)) return CB_EINVAL;
+  if (c->m.weight_format == CB_W_INT8 && !scales_ok(w)) return scales_ok_status(w);
   if (layer < 0 || layer >= c->m.n_layers) return CB_EINVAL;
   if (n_rows < 0 || n_suffix < 0 || n_suffix > n_rows) return CB_EINVAL;
   if (k_keep < 0 || k_keep > n_rows - n_suffix) return CB_EINVAL;
   if (n_tokens_total < 1 || n_tokens_total > c->max_tokens || n_rows > n_tokens_total) return CB_EINVAL;
+  return CB_OK;
+}
+
+// The matrices a projection launch reads.  Native weights: the caller's pointers.  int8 weights:
+// each matrix is expanded to bf16 into the staging area first (one after the other, so that the
+// matrices of one launch lie side by side) and the launch reads the expansion.
+struct WeightView { const void *w[3]; };
+int stage_weights(cb_ctx *c, hipStream_t s, const LayerWs &ws, int n, const void *const *w,
+                  const float *const *scale, const int *rows, int cols, WeightView *out) {
+  if (c->m.weight_format != CB_W_INT8) {
+    for (int i = 0; i < n; ++i) out->w[i] = w[i];
+    return CB_OK;
+  }
+  size_t off = 0, bytes = 0;
+  for (int i = 0; i < n; ++i) bytes += (size_t)rows[i] * cols * 3;
+  ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)bytes);
+  for (int i = 0; i < n; ++i) {
+    char *dst = (char *)ws.wstage + off;
+    CB_HIP(launch_dequant_int8(w[i], scale[i], dst, rows[i], cols, s));
+    out->w[i] = dst;
+    off += align_up((size_t)rows[i] * cols * 2, 256);
+  }
   return CB_OK;
 }
 
@@ -260,6 +300,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   g.a = ws.xn; g.lda = xld; g.a_lo_off = lo_off; g.K = d; g.epi = EPI_SEG;
   const int32_t *sel_rows = nullptr;
   bool q_all = false;
+  WeightView wv = {};
   if (check) {
     // K/V of every row that reached this layer (Sec. 6: the KV computed anew on this layer), and in
     // the launch that finishes them the deviation of every candidate from its cached K/V.
@@ -268,9 +309,15 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     // projected after the selection, for the kept rows only.
     q_all = (long)n * 4 <= (long)rows * 5;
     g.a_rows = nullptr; g.M = n; g.n_seg = q_all ? 3 : 2;
-    g.seg[0] = {w->wk, kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1, kc};
-    g.seg[1] = {w->wv, kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0, vc};
-    g.seg[2] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
+    {
+      const void *wm[3] = {w->wk, w->wv, w->wq};
+      const float *sc[3] = {w->wk_scale, w->wv_scale, w->wq_scale};
+      const int wr[3] = {kv_dim, kv_dim, q_dim};
+      CB_TRY(stage_weights(c, s, ws, g.n_seg, wm, sc, wr, d, &wv));
+    }
+    g.seg[0] = {wv.w[0], kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1, kc};
+    g.seg[1] = {wv.w[1], kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0, vc};
+    g.seg[2] = {wv.w[2], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
     g.row_pos = row_pos;
     float *dev = dev_out ? dev_out : ws.dev;
     // one request: its candidates are the leading rows; several: every row gets a value (a
@@ -308,7 +355,13 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     sel_rows = ws.sel_rows;
     if (!q_all) {
       g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
-      g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
+      {
+        const void *wm[1] = {w->wq};
+        const float *sc[1] = {w->wq_scale};
+        const int wr[1] = {q_dim};
+        CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, d, &wv));
+      }
+      g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
       g.row_pos = pos_out;
       CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * rows * d * q_dim,
                       ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es, 0));
@@ -322,9 +375,15 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
         CB_HIP(hipMemcpyAsync(cache_row_out, crow, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
     }
     g.a_rows = nullptr; g.M = n; g.n_seg = 3;
-    g.seg[0] = {w->wq, q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
-    g.seg[1] = {w->wk, kv_dim, kc, kv_dim, crow, 1, nullptr};
-    g.seg[2] = {w->wv, kv_dim, vc, kv_dim, crow, 0, nullptr};
+    {
+      const void *wm[3] = {w->wq, w->wk, w->wv};
+      const float *sc[3] = {w->wq_scale, w->wk_scale, w->wv_scale};
+      const int wr[3] = {q_dim, kv_dim, kv_dim};
+      CB_TRY(stage_weights(c, s, ws, 3, wm, sc, wr, d, &wv));
+    }
+    g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
+    g.seg[1] = {wv.w[1], kv_dim, kc, kv_dim, crow, 1, nullptr};
+    g.seg[2] = {wv.w[2], kv_dim, vc, kv_dim, crow, 0, nullptr};
     g.row_pos = row_pos;
     CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * n * d * (q_dim + 2 * kv_dim),
                     ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es, 0));
@@ -347,7 +406,13 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   // hmid = H + o Wo^T, and its RMSNorm (the MLP's input) from the launch that finishes it
   GemmArgs f = {};
   f.dtype = dt; f.a = ws.obuf; f.lda = q_dim; f.M = rows; f.K = q_dim; f.epi = EPI_F32; f.n_seg = 1;
-  f.seg[0].w = w->wo; f.seg[0].n = d;
+  {
+    const void *wm[1] = {w->wo};
+    const float *sc[1] = {w->wo_scale};
+    const int wr[1] = {d};
+    CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, q_dim, &wv));
+  }
+  f.seg[0].w = wv.w[0]; f.seg[0].n = d;
   f.out_f32 = ws.hmid; f.resid = h_in; f.resid_rows = sel_rows;
   f.norm_gain = w->mlp_norm; f.norm_out = ws.xn2; f.norm_ld = d; f.norm_lo_off = 0; f.norm_eps = m.rms_eps;
   f.partial = ws.partial; f.partial_floats = ws.partial_floats;
@@ -355,13 +420,25 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
                   (double)rows * d * (12 + es)));
   GemmArgs u = {};
   u.dtype = dt; u.a = ws.xn2; u.lda = d; u.M = rows; u.K = d; u.epi = EPI_SWIGLU; u.n_seg = 2;
-  u.seg[0] = {w->w_gate, F, ws.act, F, nullptr, 0, nullptr};
-  u.seg[1] = {w->w_up, F, nullptr, 0, nullptr, 0, nullptr};
+  {
+    const void *wm[2] = {w->w_gate, w->w_up};
+    const float *sc[2] = {w->w_gate_scale, w->w_up_scale};
+    const int wr[2] = {F, F};
+    CB_TRY(stage_weights(c, s, ws, 2, wm, sc, wr, d, &wv));
+  }
+  u.seg[0] = {wv.w[0], F, ws.act, F, nullptr, 0, nullptr};
+  u.seg[1] = {wv.w[1], F, nullptr, 0, nullptr, 0, nullptr};
   u.partial = ws.partial; u.partial_floats = ws.partial_floats;
   CB_TRY(run_gemm(c, s, u, CB_PROF_REDUCE, 2.0 * rows * d * 2 * F,
                   ((double)2 * F * d + (double)rows * d + (double)rows * F) * es, 0));
   // h_out = hmid + act Wd^T; the next layer's normalised input comes from the same finish launch
-  f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = w->w_down;
+  {
+    const void *wm[1] = {w->w_down};
+    const float *sc[1] = {w->w_down_scale};
+    const int wr[1] = {d};
+    CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, F, &wv));
+  }
+  f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = wv.w[0];
   f.out_f32 = h_out; f.resid = ws.hmid; f.resid_rows = nullptr;
   f.norm_gain = next_gain; f.norm_out = ws.xn; f.norm_ld = xld; f.norm_lo_off = lo_off;
   CB_TRY(run_gemm(c, s, f, CB_PROF_REDUCE, 2.0 * rows * F * d, ((double)F * d + (double)rows * F) * es,
@@ -395,6 +472,10 @@ int cb_create(const cb_model_desc *desc, int32_t max_tokens, cb_ctx **out) {
     return CB_EINVAL;
   if (m.dtype != CB_F32 && m.dtype != CB_BF16) return CB_EINVAL;
   if (m.rope_layout != CB_ROPE_ADJACENT && m.rope_layout != CB_ROPE_HALF) return CB_EINVAL;
+  if (m.weight_format != CB_W_NATIVE && m.weight_format != CB_W_INT8) return CB_EINVAL;
+  // int8 weights are expanded 16 at a time into bf16
+  if (m.weight_format == CB_W_INT8 && (m.dtype != CB_BF16 || m.d_model % 16 != 0 || m.d_ff % 16 != 0))
+    return CB_EUNSUPPORTED;
   if (m.head_dim != 64 && m.head_dim != 128) return CB_EUNSUPPORTED;
   if (m.n_q_heads % m.n_kv_heads != 0) return CB_EUNSUPPORTED;
   if (m.d_model % 8 != 0 || m.d_ff % 8 != 0) return CB_EUNSUPPORTED;  // 16-byte operand vectors
@@ -749,6 +830,7 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
     if (!w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->mlp_norm || !w->w_gate || !w->w_up ||
         !w->w_down)
       return CB_ENULL;
+    if (c->m.weight_format == CB_W_INT8 && !scales_ok(w)) return scales_ok_status(w);
     if (!weights_aligned(w) || !aligned(k_cache_layers[l], 16) || !aligned(v_cache_layers[l], 16) ||
         (dev_dump && !aligned(dev_dump[l], 4)))
       return CB_EINVAL;

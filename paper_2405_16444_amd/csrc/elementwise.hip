@@ -146,6 +146,44 @@ hipError_t launch_realign(int dtype, void *const *k_layers, int n_layers, const 
 }
 
 // ---------------------------------------------------------------------------
+// 8-bit weights (the paper serves its larger models with 8-bit weights, Sec. 7.1): expands an int8
+// matrix [rows, cols] with one float scale per row to bf16, out[r][c] = bf16(q[r][c] * scale[r]),
+// 16 elements per lane (a 16-byte load, two 16-byte stores).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dequant_int8_kernel(const int8_t *__restrict__ q,
+                                                           const float *__restrict__ scale,
+                                                           bf16 *__restrict__ out, size_t n16, int cols16) {
+  typedef __attribute__((ext_vector_type(4))) int i32x4;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n16; i += stride) {
+    const i32x4 w = reinterpret_cast<const i32x4 *>(q)[i];
+    const float sc = scale[i / cols16];
+    bf16x8 lo, hi;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int word = w[j];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const float v = (float)((word << (24 - 8 * b)) >> 24) * sc;      // sign-extended byte b
+        const int e = 4 * j + b;
+        if (e < 8) lo[e] = (bf16)v; else hi[e - 8] = (bf16)v;
+      }
+    }
+    reinterpret_cast<bf16x8 *>(out)[2 * i] = lo;
+    reinterpret_cast<bf16x8 *>(out)[2 * i + 1] = hi;
+  }
+}
+hipError_t launch_dequant_int8(const void *q, const float *scale, void *out, int rows, int cols, hipStream_t s) {
+  if (rows == 0 || cols == 0) return hipSuccess;
+  const size_t n16 = (size_t)rows * cols / 16;           // cols % 16 == 0 (checked by the caller)
+  const int blocks = (int)std::min<size_t>((n16 + 255) / 256, 1 << 20);
+  hipLaunchKernelGGL(dequant_int8_kernel, dim3(blocks), dim3(256), 0, s, (const int8_t *)q, scale, (bf16 *)out, n16,
+                     cols / 16);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 template <typename T>
 __global__ void to_f32_kernel(const T *__restrict__ x, float *__restrict__ out, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -14,6 +14,8 @@ hipError_t launch_realign(int dtype, void *const *k_layers_host, int n_layers,
                           const int32_t *chunk_offsets_host, int n_chunks, int kv_dim,
                           int head_dim, int rope_half, const float2 *rope_tab, hipStream_t s);
 hipError_t launch_to_f32(int dtype, const void *x, float *out, size_t n, hipStream_t s);
+// out[r][c] = bf16(q[r][c] * scale[r]) for an int8 matrix [rows, cols], cols % 16 == 0.
+hipError_t launch_dequant_int8(const void *q, const float *scale, void *out, int rows, int cols, hipStream_t s);
 // out[r] = rmsnorm(h[r]) * gain, r < n_rows; out has storage type and row pitch ld_out;
 // lo_off > 0: the rounding remainder of every value is stored lo_off elements after it.
 hipError_t launch_rmsnorm(int dtype, const float *h, const void *gain, void *out, int ld_out, int lo_off,

@@ -630,3 +630,47 @@ def test_attention_deviation_shrinks_as_more_tokens_are_recomputed():
 def rng_queries(w, seed):
     rng = np.random.default_rng(seed)
     return rng.standard_normal((w.n_suffix, w.model.n_q_heads, w.model.head_dim))
+
+
+# --------------------------------------------------------------------------- #
+# 8-bit weights: w = q * scale per output feature (Sec. 7.1; scheme = this build's reading)
+# --------------------------------------------------------------------------- #
+def test_dequantize_int8_hand_values_and_passthrough():
+    lw = {"wq": np.array([[1, -2, 0], [127, -127, 64]], dtype=np.int8), "wq_scale": np.array([0.5, 0.01], dtype=np.float32),
+          "attn_norm": np.array([1.0, 2.0, 3.0])}
+    out = O.dequantize_int8(lw)
+    assert set(out) == {"wq", "attn_norm"}
+    # written out by hand: row 0 times 0.5, row 1 times float32(0.01)
+    s1 = float(np.float32(0.01))
+    assert np.array_equal(out["wq"], np.array([[0.5, -1.0, 0.0], [127 * s1, -127 * s1, 64 * s1]]))
+    assert np.array_equal(out["attn_norm"], lw["attn_norm"])          # no scale -> untouched
+
+
+def test_dequantised_layer_equals_the_layer_on_representable_weights():
+    """A matrix whose entries ARE q * scale goes through the 8-bit route and the plain route to the same
+    block output, and the per-row scale acts on OUTPUT features: scaling row o of Wv by 2 doubles
+    channel o of v (a transposed scale would double an input feature instead)."""
+    import torch
+    from workloads import synth
+    from workloads.configs import ModelShape
+    m = ModelShape(1, 64, 2, 1, 32, 96, 1e-5, 1e4, "f32")
+    lw = {k: v for k, v in synth.layer_weights(m, 0, 4242).items()}
+    lw8 = synth.quantize_int8(lw)
+    deq = O.dequantize_int8({k: synth.to_f64(v) for k, v in lw8.items()})
+    plain = {k: (v if not k.startswith("w") else deq[k]) for k, v in deq.items()}
+    h = synth.to_f64(synth.random_rows(9, 64, 1.0, 5))
+    pos = np.arange(9)
+    x1, k1, v1 = O.project_kv(h, pos, deq, m)
+    x2, k2, v2 = O.project_kv(h, pos, plain, m)
+    assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
+    lw8b = dict(lw8)
+    sc = lw8["wv_scale"].clone()
+    sc[3] *= 2.0
+    lw8b["wv_scale"] = sc
+    deq_b = O.dequantize_int8({k: synth.to_f64(v) for k, v in lw8b.items()})
+    _, _, v3 = O.project_kv(h, pos, deq_b, m)
+    v1f, v3f = v1.reshape(9, -1), v3.reshape(9, -1)
+    assert np.allclose(v3f[:, 3], 2.0 * v1f[:, 3], rtol=1e-12) and np.array_equal(np.delete(v3f, 3, 1), np.delete(v1f, 3, 1))
+    # the quantiser of the input recipe keeps every entry within half a step of the original
+    w = synth.to_f64(lw["wq"])
+    assert np.all(np.abs(deq["wq"] - w) <= 0.5 * synth.to_f64(lw8["wq_scale"])[:, None] * (1 + 1e-6))

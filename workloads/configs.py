@@ -26,6 +26,7 @@ class ModelShape:
     dtype: str = "bf16"  # "f32" or "bf16": storage type of weights, inputs, caches
     vocab: int = 32000   # rows of the vocabulary projection (first-token head only)
     rope_layout: str = "adjacent"   # rotary pairs (2i, 2i+1) as in the paper's Appendix A, or "half": (i, i + dh/2)
+    weight_format: str = "native"   # "int8": projection matrices stored as int8 with one float scale per output feature
 
     @property
     def q_dim(self) -> int:

@@ -51,6 +51,23 @@ def layer_weights(model: ModelShape, layer: int, seed: int, device="cpu"):
     return out
 
 
+def quantize_int8(lw):
+    """The same layer with every projection matrix stored as int8 plus one float scale per output
+    feature (row): scale = max|row| / 127, q = round(w / scale).  Part of the input recipe of the 8-bit
+    workloads (the paper serves its larger models 8-bit and names no scheme); what the stored pair MEANS,
+    w = q * scale, is the consumer's business."""
+    out = {}
+    for name, t in lw.items():
+        if name.startswith("w"):
+            w = t.float()
+            scale = (w.abs().amax(dim=1).clamp_min(1e-12) / 127.0).contiguous()
+            out[name] = torch.round(w / scale[:, None]).clamp(-127, 127).to(torch.int8).contiguous()
+            out[name + "_scale"] = scale
+        else:
+            out[name] = t
+    return out
+
+
 def head_weights(model: ModelShape, seed: int, device="cpu"):
     """Final norm gain (ones) and vocabulary projection [vocab, d] ~ N(0, 0.02^2)."""
     dt = storage_dtype(model)
