@@ -36,6 +36,7 @@ struct cb_ctx {
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> free_events;
   std::vector<hipEvent_t> load_events;   // pipelined loading: [0] = entry fence, [1 + l] = layer l landed
+  std::vector<int32_t> seg_tab_host;     // batched calls: host copy of the request tables being uploaded
   mutable std::vector<size_t> partial_memo;   // [rows] -> scratch floats layer calls with <= rows rows can use
   void *static_scratch;                  // this device's copy of the built-in scratch array (cb_fuse_layer_static)
 };
@@ -273,7 +274,8 @@ int run_gemm(cb_ctx *c, hipStream_t s, const GemmArgs &g, int finish_class, doub
 int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, const int32_t *row_pos,
                     const int32_t *cache_row, const Seg *segs, int n_segs, size_t cache_stride, void *kc,
                     void *vc, const int32_t *forced, float *h_out, int32_t *pos_out, int32_t *cache_row_out,
-                    float *dev_out, const LayerWs &ws, hipStream_t s, bool xn_ready, const void *next_gain) {
+                    float *dev_out, const LayerWs &ws, hipStream_t s, bool xn_ready, const void *next_gain,
+                    const int32_t *seg_dev = nullptr) {
   const cb_model_desc &m = c->m;
   const int dt = m.dtype;
   const size_t es = esize(c);
@@ -339,9 +341,14 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
         CB_HIP(launch_scatter_kv(dt, ws.kvnew, ws.sel_rows, cache_row_out ? cache_row_out : pos_out, rows, kc, vc,
                                  kv_dim, s));
       } else {
-        // selection and the update of the kept tokens' KV (Sec. 6) in one launch per request
-        int in_off = 0, out_off = 0;
-        for (int b = 0; b < n_segs; ++b) {
+        // selection and the update of the kept tokens' KV (Sec. 6) in one launch: one request, or all
+        // requests of the call through the device table; without a table, a launch per request
+        int in_off = 0, out_off = 0, max_out = 0;
+        for (int b = 0; b < n_segs; ++b) max_out = std::max(max_out, segs[b].k + segs[b].S);
+        if (seg_dev)
+          CB_HIP(launch_topk_scatter(dev, 0, 0, 0, row_pos, cache_row, ws.sel_rows, pos_out, cache_row_out, 0,
+                                     ws.kvnew, kc, vc, (int)(kv_dim * es), s, seg_dev, n_segs, max_out));
+        for (int b = 0; b < n_segs && !seg_dev; ++b) {
           CB_HIP(launch_topk_scatter(dev + in_off, segs[b].n - segs[b].S, segs[b].k, segs[b].S, row_pos + in_off,
                                      cache_row ? cache_row + in_off : nullptr, ws.sel_rows + out_off,
                                      pos_out + out_off, cache_row_out ? cache_row_out + out_off : nullptr, in_off,
@@ -389,10 +396,23 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
                     ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es, 0));
   }
   {
-    // attention is per request: its rows against its own cache slab
+    // attention is per request: its rows against its own cache slab -- all requests in one launch
+    // through the device table (bf16), else a launch per request
     ProfScope ps(c, s, CB_PROF_ATTN, 0, 0);
     int out_off = 0;
-    for (int b = 0; b < n_segs; ++b) {
+    const bool varlen = seg_dev && dt == CB_BF16;
+    if (varlen) {
+      long total_qwg = 0;
+      int max_t = 0;
+      for (int b = 0; b < n_segs; ++b) {
+        total_qwg += attention_query_workgroups(segs[b].k + segs[b].S, m.n_q_heads, m.n_kv_heads);
+        max_t = std::max(max_t, segs[b].T);
+      }
+      CB_HIP(launch_attention(dt, ws.qbuf, q_all ? sel_rows : nullptr, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads,
+                              m.n_kv_heads, m.head_dim, max_t, ws.partial, ws.partial_floats, s, seg_dev, n_segs,
+                              total_qwg));
+    }
+    for (int b = 0; b < n_segs && !varlen; ++b) {
       const int rows_b = segs[b].k + segs[b].S;
       const char *q_b = (const char *)ws.qbuf + (q_all ? 0 : (size_t)out_off * q_dim * es);
       CB_HIP(launch_attention(dt, q_b, q_all ? sel_rows + out_off : nullptr, pos_out + out_off, rows_b,
@@ -786,7 +806,9 @@ size_t cb_batched_workspace_bytes(const cb_ctx *c, int32_t total_tokens) {
   if (!c || total_tokens < 1) return 0;
   const size_t h = align_up((size_t)total_tokens * c->m.d_model * 4, 256);
   const size_t p = align_up((size_t)total_tokens * 4, 256);
-  return 2 * h + 4 * p + carve_layer(c, nullptr, total_tokens).bytes;
+  // + the per-layer request tables (at most one request per token)
+  const size_t tab = align_up((size_t)c->m.n_layers * ((size_t)total_tokens + 1) * kSegInts * 4, 256);
+  return 2 * h + 4 * p + tab + carve_layer(c, nullptr, total_tokens).bytes;
 }
 
 int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n_requests, const void *x,
@@ -847,7 +869,34 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
   float *h_cur = (float *)base, *h_nxt = (float *)(base + hb);
   int32_t *p_cur = (int32_t *)(base + 2 * hb), *p_nxt = (int32_t *)(base + 2 * hb + pb);
   int32_t *r_cur = (int32_t *)(base + 2 * hb + 2 * pb), *r_nxt = (int32_t *)(base + 2 * hb + 3 * pb);
-  LayerWs ws = carve_layer(c, base + 2 * hb + 4 * pb, N);
+  int32_t *seg_tab = (int32_t *)(base + 2 * hb + 4 * pb);
+  const size_t tab_bytes = align_up((size_t)L * ((size_t)N + 1) * kSegInts * 4, 256);
+  LayerWs ws = carve_layer(c, base + 2 * hb + 4 * pb + tab_bytes, N);
+
+  // Request tables of every layer (the keep counts are inputs, so all of them are known now), built
+  // on the host and uploaded once: selection and attention then take all requests in one launch each.
+  std::vector<int32_t> &tab = c->seg_tab_host;       // outlives the call: the upload below may read it later
+  tab.assign((size_t)L * (B + 1) * kSegInts, 0);
+  {
+    std::vector<int> n_in(B);
+    for (int b = 0; b < B; ++b) n_in[b] = T[b];
+    for (int l = 0; l < L; ++l) {
+      int in_off = 0, out_off = 0;
+      long qwg = 0;
+      for (int b = 0; b <= B; ++b) {
+        int32_t *e = &tab[((size_t)l * (B + 1) + b) * kSegInts];
+        e[kSegInOff] = in_off; e[kSegOutOff] = out_off; e[kSegQwg] = (int32_t)qwg;
+        if (b == B) break;
+        const int S = n_suffix[b], k = keep_counts[(size_t)b * L + l];
+        e[kSegCand] = n_in[b] - S; e[kSegKeep] = k; e[kSegSuffix] = S; e[kSegCacheRow] = b * cache_stride;
+        in_off += n_in[b];
+        out_off += k + S;
+        qwg += attention_query_workgroups(k + S, c->m.n_q_heads, c->m.n_kv_heads);
+        n_in[b] = k + S;
+      }
+    }
+  }
+  if (B > 1) CB_HIP(hipMemcpyAsync(seg_tab, tab.data(), tab.size() * 4, hipMemcpyHostToDevice, s));
 
   {
     ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)N * d * (4 + es));
@@ -874,7 +923,8 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
     int st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, r_cur, segs.data(), B, (size_t)cache_stride,
                              k_cache_layers[l], v_cache_layers[l], nullptr, h_nxt, p_nxt, r_nxt,
                              dev_dump ? dev_dump[l] : nullptr, ws, s, l > 0,
-                             l + 1 < L ? layers[l + 1].attn_norm : nullptr);
+                             l + 1 < L ? layers[l + 1].attn_norm : nullptr,
+                             B > 1 ? seg_tab + (size_t)l * (B + 1) * kSegInts : nullptr);
     if (st != CB_OK) return st;
     int o = 0;
     for (int b = 0; b < B; ++b) {

@@ -43,7 +43,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
                                                         int split_tiles, float *__restrict__ part_o,
                                                         float *__restrict__ part_ml,
                                                         const int32_t *__restrict__ q_rows,
-                                                        int32_t *__restrict__ wg_tiles) {
+                                                        int32_t *__restrict__ wg_tiles,
+                                                        const int32_t *__restrict__ segs, int n_segs) {
   // K and V tiles sit row-major in LDS ([key][channel], no padding) and are filled by direct
   // global->LDS loads: one wavefront-wide 16-byte load writes 1 KB = RPI whole rows.  Instead of
   // padding, the 16-byte chunk c of row r is stored in slot c ^ f(r), which makes both the
@@ -63,10 +64,32 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
   const int ln = lane & 31, h = lane >> 5;
   const int g = n_q_heads / n_kv_heads;
   const int kvh = blockIdx.x;                          // kv head varies fastest in dispatch order
-  const int n_flat = n_rows * g;
-  // workgroups with the longest key range (the last rows) are dispatched first, for every kv head
-  const int m_wg = (int)(gridDim.y - 1 - blockIdx.y) * WGQ;
   const int kv_dim = n_kv_heads * DH;
+  // workgroups with the longest key range (the last rows) are dispatched first, for every kv head
+  const int qwg = (int)(gridDim.y - 1 - blockIdx.y);
+  // Several requests in one launch: request s owns the query workgroups [segs[s].qwg, segs[s+1].qwg),
+  // the rows [row0, row0 + rows) of q_pos / q_rows / o, and the cache rows from cache0 on.
+  int seg_qwg0 = 0, row0 = 0;
+  if (segs) {
+    int lo = 0, hi = n_segs - 1;                       // last segment whose first workgroup is <= qwg
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (segs[mid * kSegInts + kSegQwg] <= qwg) lo = mid; else hi = mid - 1;
+    }
+    const int32_t *sg = segs + lo * kSegInts;
+    seg_qwg0 = sg[kSegQwg];
+    row0 = sg[kSegOutOff];
+    n_rows = sg[kSegKeep] + sg[kSegSuffix];
+    const size_t cache0 = (size_t)sg[kSegCacheRow] * kv_dim;
+    kc += cache0;
+    vc += cache0;
+    q_pos += row0;
+    if (q_rows) q_rows += row0;
+  }
+  const int n_flat = n_rows * g;
+  const int m_wg = (qwg - seg_qwg0) * WGQ;             // first flattened query of the workgroup, within its request
+  const int m_pad = qwg * WGQ;                         // the same in the launch-wide numbering of the scratch
+  const int n_flat_pad = (int)gridDim.y * WGQ;
 
   // causal bound of the workgroup = largest position among its rows (they need not be sorted)
   __shared__ int s_max_pos;
@@ -83,7 +106,7 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
   const int kv_len = s_max_pos + 1;
   const int n_tiles_all = (kv_len + BKV - 1) / BKV;
   // the merge launch needs the same bound to know which pieces of the key range ran
-  if (gridDim.z > 1 && kvh == 0 && blockIdx.z == 0 && tid == 0) wg_tiles[gridDim.y - 1 - blockIdx.y] = n_tiles_all;
+  if (gridDim.z > 1 && kvh == 0 && blockIdx.z == 0 && tid == 0) wg_tiles[qwg] = n_tiles_all;
   // KV split: workgroup z of gridDim.z handles tiles [t_begin, n_tiles) of the causal range and
   // leaves un-normalised partial results (flash-decoding style) for the merge kernel
   const int t_begin = blockIdx.z * split_tiles;
@@ -103,8 +126,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
     const int mm = valid[b] ? m : n_flat - 1;
     const int r = mm / g, j = mm - r * g;
     my_pos[b] = valid[b] ? q_pos[r] : -1;
-    q_off[b] = ((long)r * n_q_heads + kvh * g + j) * DH;
-    const long q_src = ((long)(q_rows ? q_rows[r] : r) * n_q_heads + kvh * g + j) * DH;
+    q_off[b] = ((long)(row0 + r) * n_q_heads + kvh * g + j) * DH;
+    const long q_src = ((long)(q_rows ? q_rows[r] : row0 + r) * n_q_heads + kvh * g + j) * DH;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
       qf[b][ks] = *reinterpret_cast<const bf16x8 *>(q + q_src + ks * 16 + 8 * h);
@@ -288,8 +311,8 @@ __global__ __launch_bounds__(64 * NW) void attn_bf16_kernel(const bf16 *__restri
     for (int b = 0; b < NQB; ++b) {
       const float tot = row_sum[b] + __shfl_xor(row_sum[b], 32, 64);
       if (!valid[b]) continue;
-      const int m = m_wg + (wave * NQB + b) * 32 + ln;
-      const size_t slot = ((size_t)kvh * n_flat + m) * gridDim.z + blockIdx.z;
+      const int m = m_pad + (wave * NQB + b) * 32 + ln;
+      const size_t slot = ((size_t)kvh * n_flat_pad + m) * gridDim.z + blockIdx.z;
       if (h == 0) {
         part_ml[slot * 2] = row_max[b] * scale_log2e;
         part_ml[slot * 2 + 1] = tot;
@@ -331,15 +354,32 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
                                                          const int32_t *__restrict__ q_pos, int n_rows,
                                                          bf16 *__restrict__ o, int n_q_heads,
                                                          int n_kv_heads, int n_splits, int split_tiles,
-                                                         int wg_queries, const int32_t *__restrict__ wg_tiles) {
+                                                         int wg_queries, const int32_t *__restrict__ wg_tiles,
+                                                         int n_flat_pad, const int32_t *__restrict__ segs,
+                                                         int n_segs) {
   constexpr int CG = DH / 4;                           // float4 channel groups per query
-  const int g = n_q_heads / n_kv_heads, n_flat = n_rows * g;
+  const int g = n_q_heads / n_kv_heads;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= (long)n_kv_heads * n_flat * CG) return;
+  if (idx >= (long)n_kv_heads * n_flat_pad * CG) return;
   const int c = (int)(idx % CG);
-  const long qh = idx / CG;                            // kvh * n_flat + m
-  const int m = (int)(qh % n_flat), kvh = (int)(qh / n_flat);
-  const int n_tiles = wg_tiles[m / wg_queries];      // key tiles of the query's workgroup
+  const long qh = idx / CG;                            // kvh * n_flat_pad + padded query number
+  const int m_pad = (int)(qh % n_flat_pad), kvh = (int)(qh / n_flat_pad);
+  const int qwg = m_pad / wg_queries;
+  int seg_qwg0 = 0, row0 = 0;
+  if (segs) {
+    int lo = 0, hi = n_segs - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (segs[mid * kSegInts + kSegQwg] <= qwg) lo = mid; else hi = mid - 1;
+    }
+    const int32_t *sg = segs + lo * kSegInts;
+    seg_qwg0 = sg[kSegQwg];
+    row0 = sg[kSegOutOff];
+    n_rows = sg[kSegKeep] + sg[kSegSuffix];
+  }
+  const int m = m_pad - seg_qwg0 * wg_queries;        // flattened query within its request
+  if (m >= n_rows * g) return;                         // padding of the request's last workgroup
+  const int n_tiles = wg_tiles[qwg];                 // key tiles of the query's workgroup
   const int ns = min(n_splits, (n_tiles + split_tiles - 1) / split_tiles);
   const float *ml = part_ml + qh * n_splits * 2;
   float mx = kNegBig;
@@ -355,7 +395,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *__restrict
   const float inv = 1.f / den;
   const int r = m / g, j = m - r * g;
   bf16x4 w4 = {(bf16)(acc.x * inv), (bf16)(acc.y * inv), (bf16)(acc.z * inv), (bf16)(acc.w * inv)};
-  *reinterpret_cast<bf16x4 *>(o + ((size_t)r * n_q_heads + kvh * g + j) * DH + c * 4) = w4;
+  *reinterpret_cast<bf16x4 *>(o + ((size_t)(row0 + r) * n_q_heads + kvh * g + j) * DH + c * 4) = w4;
 }
 
 // ---------------------------------------------------------------------------
@@ -425,10 +465,9 @@ constexpr int ATT_NW = 8, ATT_WGQ = 32 * ATT_NW;
 // (workgroup z takes tiles [z*split_tiles, (z+1)*split_tiles) and exits when its own causal
 // range ends before that).  Measured on 359..986-row layers: about one round of 256 workgroups
 // in total is the optimum; more pieces cost more in partial results than they gain in balance.
-static void attn_split_plan(int n_rows, int hq, int hkv, int dh, int n_tokens, int *n_splits, int *split_tiles) {
-  (void)dh;
-  const long n_flat = (long)n_rows * (hq / hkv);
-  const long base = ((n_flat + ATT_WGQ - 1) / ATT_WGQ) * hkv;
+// n_qwg: query workgroups per kv head.
+static void attn_split_plan(long n_qwg, int hkv, int n_tokens, int *n_splits, int *split_tiles) {
+  const long base = n_qwg * hkv;
   const int max_tiles = (n_tokens + BKV - 1) / BKV;
   int ns = 1;
   if (base < 128) {
@@ -442,37 +481,45 @@ static void attn_split_plan(int n_rows, int hq, int hkv, int dh, int n_tokens, i
   *n_splits = (max_tiles + *split_tiles - 1) / *split_tiles;
 }
 
-// scratch of a launch with ns key-range pieces: partial O, (max, sum) pairs, and one key-tile
-// count per query workgroup
-static size_t attn_scratch_floats(int n_rows, int hq, int hkv, int dh, int ns) {
-  const long n_flat = (long)n_rows * (hq / hkv);
-  return (size_t)n_rows * hq * ns * (dh + 2) + (size_t)((n_flat + ATT_WGQ - 1) / ATT_WGQ);
+static long query_workgroups(int n_rows, int hq, int hkv) {
+  return ((long)n_rows * (hq / hkv) + ATT_WGQ - 1) / ATT_WGQ;
+}
+
+// scratch of a launch with n_qwg query workgroups per kv head and ns key-range pieces: partial O
+// and (max, sum) pairs per (kv head, padded query, piece), and one key-tile count per query workgroup
+static size_t attn_scratch_floats(long n_qwg, int hkv, int dh, int ns) {
+  return (size_t)hkv * n_qwg * ATT_WGQ * ns * (dh + 2) + (size_t)n_qwg;
 }
 
 size_t attention_partial_floats(int dtype, int n_rows, int hq, int hkv, int dh, int n_tokens) {
   if (dtype == 0 || n_rows == 0) return 0;
   int ns, st;
-  attn_split_plan(n_rows, hq, hkv, dh, n_tokens, &ns, &st);
+  const long n_qwg = query_workgroups(n_rows, hq, hkv);
+  attn_split_plan(n_qwg, hkv, n_tokens, &ns, &st);
   if (ns <= 1) return 0;
-  return attn_scratch_floats(n_rows, hq, hkv, dh, ns);
+  return attn_scratch_floats(n_qwg, hkv, dh, ns);
 }
 
 // The same for ANY cache length: the piece count never exceeds what the row count alone allows.
 size_t attention_partial_floats_bound(int dtype, int n_rows, int hq, int hkv, int dh) {
   if (dtype == 0 || n_rows == 0) return 0;
-  const long n_flat = (long)n_rows * (hq / hkv);
-  const long base = ((n_flat + ATT_WGQ - 1) / ATT_WGQ) * hkv;
+  const long n_qwg = query_workgroups(n_rows, hq, hkv);
+  const long base = n_qwg * hkv;
   const int ns = base < 128 ? (int)std::min<long>(32, (256 + base - 1) / base) : (base < 256 ? 2 : 1);
   if (ns <= 1) return 0;
-  return attn_scratch_floats(n_rows, hq, hkv, dh, ns);
+  return attn_scratch_floats(n_qwg, hkv, dh, ns);
 }
+
+long attention_query_workgroups(int n_rows, int hq, int hkv) { return query_workgroups(n_rows, hq, hkv); }
 
 hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, const int32_t *q_pos, int n_rows,
                             const void *kc, const void *vc, void *o, int hq, int hkv, int dh,
-                            int n_tokens, float *partial, size_t partial_floats, hipStream_t s) {
+                            int n_tokens, float *partial, size_t partial_floats, hipStream_t s,
+                            const int32_t *segs, int n_segs, long total_qwg) {
   if (n_rows == 0) return hipSuccess;
   const float scale_log2e = kLog2e / sqrtf((float)dh);
   if (dtype == 0) {
+    if (segs) return hipErrorInvalidValue;           // the float kernel takes one request per launch
     dim3 grid((n_rows * hq + 3) / 4);
     if (dh == 64)
       hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, s, (const float *)q, q_pos, n_rows,
@@ -482,18 +529,21 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
                          (const float *)kc, (const float *)vc, (float *)o, hq, hkv, scale_log2e, q_rows);
     return hipGetLastError();
   }
-  const int g = hq / hkv;
-  const long n_flat = (long)n_rows * g;
+  const long n_qwg = segs ? total_qwg : query_workgroups(n_rows, hq, hkv);
   int n_splits, split_tiles;
-  attn_split_plan(n_rows, hq, hkv, dh, n_tokens, &n_splits, &split_tiles);
-  if (n_splits > 1 && (!partial || partial_floats < attn_scratch_floats(n_rows, hq, hkv, dh, n_splits))) {
-    n_splits = 1;                                    // no scratch: one workgroup walks all keys
-    split_tiles = (n_tokens + BKV - 1) / BKV;
+  attn_split_plan(n_qwg, hkv, n_tokens, &n_splits, &split_tiles);
+  while (n_splits > 1 && (!partial || partial_floats < attn_scratch_floats(n_qwg, hkv, dh, n_splits))) {
+    // scratch is short: fewer, longer pieces (down to one workgroup walking all keys)
+    const int max_tiles = (n_tokens + BKV - 1) / BKV;
+    const int ns = n_splits - 1;
+    split_tiles = (max_tiles + ns - 1) / ns;
+    n_splits = (max_tiles + split_tiles - 1) / split_tiles;
   }
   const int wgq = ATT_WGQ;
+  const size_t slots = (size_t)hkv * n_qwg * ATT_WGQ * n_splits;
   float *part_o = partial;
-  float *part_ml = partial ? partial + (size_t)n_rows * hq * n_splits * dh : nullptr;
-  int32_t *wg_tiles = partial ? reinterpret_cast<int32_t *>(part_ml + (size_t)n_rows * hq * n_splits * 2) : nullptr;
+  float *part_ml = partial ? partial + slots * dh : nullptr;
+  int32_t *wg_tiles = partial ? reinterpret_cast<int32_t *>(part_ml + slots * 2) : nullptr;
 #define CB_ATTN(DH_, NQB_, NW_)                                                                     \
   do {                                                                                              \
     constexpr int smem = ATT_S * 2 * BKV * DH_ * 2;                                                 \
@@ -502,25 +552,25 @@ hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, con
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<DH_, NQB_, NW_>),  \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);                  \
     });                                                                                             \
-    hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_, NW_>),                                          \
-                       dim3(hkv, (unsigned)((n_flat + wgq - 1) / wgq), n_splits), dim3(64 * NW_),   \
-                       smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc, (const bf16 *)vc, \
-                       (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o, part_ml, q_rows,       \
-                       wg_tiles);                                                                   \
+    hipLaunchKernelGGL((attn_bf16_kernel<DH_, NQB_, NW_>), dim3(hkv, (unsigned)n_qwg, n_splits),    \
+                       dim3(64 * NW_), smem, s, (const bf16 *)q, q_pos, n_rows, (const bf16 *)kc,   \
+                       (const bf16 *)vc, (bf16 *)o, hq, hkv, scale_log2e, split_tiles, part_o,      \
+                       part_ml, q_rows, wg_tiles, segs, n_segs);                                    \
   } while (0)
   if (dh == 64) CB_ATTN(64, 1, ATT_NW);
   else CB_ATTN(128, 1, ATT_NW);
 #undef CB_ATTN
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || n_splits == 1) return e;
-  const long total = (long)hkv * n_flat * (dh / 4);
+  const int n_flat_pad = (int)n_qwg * ATT_WGQ;
+  const long total = (long)hkv * n_flat_pad * (dh / 4);
   const dim3 mgrid((unsigned)((total + 255) / 256));
   if (dh == 64)
     hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
-                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq, wg_tiles);
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq, wg_tiles, n_flat_pad, segs, n_segs);
   else
     hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(256), 0, s, part_o, part_ml, q_pos, n_rows,
-                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq, wg_tiles);
+                       (bf16 *)o, hq, hkv, n_splits, split_tiles, wgq, wg_tiles, n_flat_pad, segs, n_segs);
   return hipGetLastError();
 }
 

@@ -6,6 +6,13 @@
 
 namespace cb {
 
+// Device table of the requests stacked in one layer call, kSegInts ints per request (+ one closing
+// entry whose kSegQwg is the total): where its rows enter (kSegInOff) and how many of them are
+// candidates / kept / suffix rows, where its kept rows start in the output (kSegOutOff), its first
+// attention query workgroup (kSegQwg) and the first row of its slab in the cache arrays.
+enum { kSegInOff = 0, kSegCand = 1, kSegKeep = 2, kSegSuffix = 3, kSegOutOff = 4, kSegQwg = 5, kSegCacheRow = 6,
+       kSegInts = 8 };
+
 // ---- elementwise.hip -------------------------------------------------------
 // In-place rotation of cached keys of chunks >= 1 by their offsets.
 // rope_tab: float2 [max_tokens][head_dim/2] = (cos, sin)(p * theta_i).
@@ -33,10 +40,14 @@ hipError_t launch_copy_rows_f32(const float *in, float *out, size_t n, hipStream
 // that row and cache_row_out[i] (nullable) = its cache row (cache_row, NULL: row_pos; both indexed
 // without row_base).  With kvnew != NULL the same launch copies the kept rows' new K/V
 // (kvnew[row_base + i] = [K | V], kv_row_bytes each, a multiple of 16) into rows cache_row of kc / vc.
+// segs (device, NULL: one request): the request table; the arrays are then the stacked ones of all
+// n_segs requests, each request's counts and offsets come from its entry (n_cand, k, n_suffix, row_base
+// are ignored) and max_out is the largest k + n_suffix of any request.
 hipError_t launch_topk_scatter(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
                                const int32_t *cache_row, int32_t *sel_rows, int32_t *pos_out,
                                int32_t *cache_row_out, int row_base, const void *kvnew, void *kc, void *vc,
-                               int kv_row_bytes, hipStream_t s);
+                               int kv_row_bytes, hipStream_t s, const int32_t *segs = nullptr, int n_segs = 0,
+                               int max_out = 0);
 // out[i] = src[idx[i]], i < n.
 hipError_t launch_gather_i32(const int32_t *src, const int32_t *idx, int n, int32_t *out, hipStream_t s);
 // Same outputs from a given ascending list of positions (lower-bound search in row_pos).
@@ -110,10 +121,16 @@ size_t attention_partial_floats(int dtype, int n_rows, int n_q_heads, int n_kv_h
                                 int n_tokens);
 // upper bound of the above over every n_tokens (for workspace sizing)
 size_t attention_partial_floats_bound(int dtype, int n_rows, int n_q_heads, int n_kv_heads, int head_dim);
+// segs (device, NULL: one request): the table above with n_segs requests; q_rows / q_pos / o are then the
+// stacked arrays of all requests, n_rows their total, n_tokens the longest cache, total_qwg the sum of
+// attention_query_workgroups over the requests (bf16 only).
 hipError_t launch_attention(int dtype, const void *q, const int32_t *q_rows, const int32_t *q_pos, int n_rows,
                             const void *k_cache, const void *v_cache, void *o, int n_q_heads,
                             int n_kv_heads, int head_dim, int n_tokens, float *partial,
-                            size_t partial_floats, hipStream_t s);
+                            size_t partial_floats, hipStream_t s, const int32_t *segs = nullptr, int n_segs = 0,
+                            long total_qwg = 0);
+// query workgroups (per kv head) a request with n_rows rows occupies in the bf16 kernel's grid
+long attention_query_workgroups(int n_rows, int n_q_heads, int n_kv_heads);
 
 // ---- head.hip ---------------------------------------------------------------
 // logits[v] = T(rmsnorm(h_row) * gain) . w[v, :], v < vocab; w row-major [vocab, d]; d % 8 == 0,

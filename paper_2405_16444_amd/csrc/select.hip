@@ -47,7 +47,19 @@ __global__ __launch_bounds__(kSelThreads) void topk_scatter_kernel(
     const float *__restrict__ dev, int n, int k, int n_suffix, const int32_t *__restrict__ row_pos,
     const int32_t *__restrict__ cache_row, int32_t *__restrict__ sel_rows, int32_t *__restrict__ pos_out,
     int32_t *__restrict__ cache_row_out, int row_base, const uint4 *__restrict__ kvnew, uint4 *__restrict__ kc,
-    uint4 *__restrict__ vc, int vec_per_row) {
+    uint4 *__restrict__ vc, int vec_per_row, const int32_t *__restrict__ segs) {
+  if (segs) {
+    // several requests in one launch: blockIdx.y names the request, its share of every array
+    // starts at its offsets in the table
+    const int32_t *sg = segs + blockIdx.y * kSegInts;
+    const int in_off = sg[kSegInOff], out_off = sg[kSegOutOff];
+    n = sg[kSegCand]; k = sg[kSegKeep]; n_suffix = sg[kSegSuffix];
+    dev += in_off; row_pos += in_off;
+    if (cache_row) cache_row += in_off;
+    sel_rows += out_off; pos_out += out_off;
+    if (cache_row_out) cache_row_out += out_off;
+    row_base = in_off;
+  }
   __shared__ unsigned hist[256];
   __shared__ unsigned s_prefix, s_need;
   __shared__ int wave_tot[kSelWaves];
@@ -146,17 +158,18 @@ __global__ __launch_bounds__(kSelThreads) void topk_scatter_kernel(
 hipError_t launch_topk_scatter(const float *dev, int n_cand, int k, int n_suffix, const int32_t *row_pos,
                                const int32_t *cache_row, int32_t *sel_rows, int32_t *pos_out,
                                int32_t *cache_row_out, int row_base, const void *kvnew, void *kc, void *vc,
-                               int kv_row_bytes, hipStream_t s) {
-  const int n_out = k + n_suffix;
+                               int kv_row_bytes, hipStream_t s, const int32_t *segs, int n_segs,
+                               int max_out) {
+  const int n_out = segs ? max_out : k + n_suffix;   // most kept + suffix rows of any request
   if (n_out == 0) return hipSuccess;
   int G = 1;
   if (kvnew) {
-    G = std::min(128, (n_out + 3) / 4);
+    G = std::min(segs ? std::max(1, 128 / n_segs) : 128, (n_out + 3) / 4);
     G = std::max(G, (n_out + kSelList - 1) / kSelList);
   }
-  hipLaunchKernelGGL(topk_scatter_kernel, dim3(G), dim3(kSelThreads), 0, s, dev, n_cand, k, n_suffix, row_pos,
-                     cache_row, sel_rows, pos_out, cache_row_out, row_base, (const uint4 *)kvnew, (uint4 *)kc,
-                     (uint4 *)vc, kv_row_bytes / 16);
+  hipLaunchKernelGGL(topk_scatter_kernel, dim3(G, segs ? n_segs : 1), dim3(kSelThreads), 0, s, dev, n_cand, k,
+                     n_suffix, row_pos, cache_row, sel_rows, pos_out, cache_row_out, row_base, (const uint4 *)kvnew,
+                     (uint4 *)kc, (uint4 *)vc, kv_row_bytes / 16, segs);
   return hipGetLastError();
 }
 

@@ -100,6 +100,11 @@ def check_request(b, r, npl, model, out, kc, vc, stride, rows_in, tol):
     ("f32", [((60, 45, 70), 7, (1.0, 0.4, 0.2)), ((33, 90), 12, (1.0, 0.5, 0.5)), ((128,), 1, (1.0, 0.3, 0.1))]),
     ("bf16", [((150, 97, 200), 21, (1.0, 0.35, 0.15)), ((64, 64, 64, 64), 32, (1.0, 0.9, 0.85))]),
     ("bf16_g7", [((80, 120), 10, (1.0, 1.0, 1.0)), ((90, 70, 50), 5, (1.0, 1.0, 1.0))]),     # no check at all
+    # eight ragged requests: selection and attention of all of them run as one launch each
+    ("bf16", [((150, 97), 21, (1.0, 0.35, 0.15)), ((64,), 1, (1.0, 0.5, 0.5)), ((33, 90, 47), 12, (1.0, 0.9, 0.85)),
+              ((200,), 0, (1.0, 0.3, 0.1)), ((17, 19, 23, 29), 5, (1.0, 0.25, 0.0)), ((128, 128), 32, (1.0, 1.0, 0.4)),
+              ((1,), 1, (1.0, 1.0, 1.0)), ((77, 301), 9, (1.0, 0.15, 0.15))]),
+    ("bf16_dh64", [((60, 45, 70), 7, (1.0, 0.4, 0.2)), ((90,), 3, (1.0, 0.5, 0.25)), ((31, 64), 16, (1.0, 0.6, 0.6))]),
 ])
 def test_batched_requests_each_match_the_oracle(P, name, specs):
     model = replace(MODELS[name], n_layers=3)
