@@ -109,7 +109,7 @@ struct LayerWs {
   size_t bytes;
 };
 
-// bf16 models feed the Q/K/V projections a (high, low) pair per normalised activation, the low
+// bf16 models feed the K/V projection a (high, low) pair per normalised activation, the low
 // parts d_model elements after the high parts of the same row
 int xn_lo_off(const cb_ctx *c) { return c->m.dtype == CB_BF16 ? c->m.d_model : 0; }
 int xn_pitch(const cb_ctx *c) { return c->m.d_model + xn_lo_off(c); }
@@ -126,10 +126,9 @@ size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
   while ((int)memo.size() <= max_rows) {
     const int M = (int)memo.size();
     size_t need = memo.back();
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 1, rh, m.head_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim + 2 * kv_dim, d, hl, 1, rh, m.head_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim, d, hl, 0, rh, m.head_dim));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim + 2 * kv_dim, d, hl, 0, rh, m.head_dim));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 1, rh, m.head_dim));   // K|V, checked
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 0, rh, m.head_dim));   // K|V, every row kept
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim, d, 0, 0, rh, m.head_dim));         // Q
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, q_dim, 0, 0, 0, 0));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, m.d_ff, 0, 0, 0, 0));
     need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, M, m.d_ff, d, 0, 0, 0, 0));
@@ -299,38 +298,32 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   GemmArgs g = {};
   g.dtype = dt; g.rope_tab = c->rope_tab; g.head_dim = m.head_dim; g.rope_half = m.rope_layout == CB_ROPE_HALF;
   g.partial = ws.partial; g.partial_floats = ws.partial_floats;
-  g.a = ws.xn; g.lda = xld; g.a_lo_off = lo_off; g.K = d; g.epi = EPI_SEG;
+  g.a = ws.xn; g.lda = xld; g.K = d; g.epi = EPI_SEG;
   const int32_t *sel_rows = nullptr;
-  bool q_all = false;
   WeightView wv = {};
+  // K and V of every row that reached this layer (Sec. 6: the KV computed anew on this layer), from the
+  // (high, low) activation pairs: an error in a stored key is multiplied by the score it takes part in,
+  // so the keys and values get a float-accurate input.  With a check they go to the workspace and the
+  // launch that finishes them also measures every candidate's deviation from its cached K/V; without
+  // one every row is kept and they are written straight into the cache.
+  g.a_rows = nullptr; g.M = n; g.n_seg = 2; g.a_lo_off = lo_off;
+  {
+    const void *wm[2] = {w->wk, w->wv};
+    const float *sc[2] = {w->wk_scale, w->wv_scale};
+    const int wr[2] = {kv_dim, kv_dim};
+    CB_TRY(stage_weights(c, s, ws, 2, wm, sc, wr, d, &wv));
+  }
+  g.row_pos = row_pos;
+  const double kv_flops = 2.0 * n * d * 2 * kv_dim, kv_bytes = ((double)2 * kv_dim * d + (double)n * d + (double)n * 2 * kv_dim) * es;
   if (check) {
-    // K/V of every row that reached this layer (Sec. 6: the KV computed anew on this layer), and in
-    // the launch that finishes them the deviation of every candidate from its cached K/V.
-    // When nearly every candidate survives (gradual filtering), Q is projected for all candidates
-    // in the same launch and attention picks the kept rows through sel_rows; otherwise Q is
-    // projected after the selection, for the kept rows only.
-    q_all = (long)n * 4 <= (long)rows * 5;
-    g.a_rows = nullptr; g.M = n; g.n_seg = q_all ? 3 : 2;
-    {
-      const void *wm[3] = {w->wk, w->wv, w->wq};
-      const float *sc[3] = {w->wk_scale, w->wv_scale, w->wq_scale};
-      const int wr[3] = {kv_dim, kv_dim, q_dim};
-      CB_TRY(stage_weights(c, s, ws, g.n_seg, wm, sc, wr, d, &wv));
-    }
     g.seg[0] = {wv.w[0], kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1, kc};
     g.seg[1] = {wv.w[1], kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0, vc};
-    g.seg[2] = {wv.w[2], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
-    g.row_pos = row_pos;
     float *dev = dev_out ? dev_out : ws.dev;
     // one request: its candidates are the leading rows; several: every row gets a value (a
     // suffix row's is never looked at)
     const int n_dev = n_segs == 1 ? n - segs[0].S : n;
     g.dev_out = dev; g.n_dev = n_dev; g.dev_row = crow;
-    const int n_out = 2 * kv_dim + (q_all ? q_dim : 0);
-    // flops counted as the method needs them: Q only for the rows that are kept
-    CB_TRY(run_gemm(c, s, g, CB_PROF_DEV, 2.0 * n * d * 2 * kv_dim + (q_all ? 2.0 * rows * d * q_dim : 0.0),
-                    ((double)n_out * d + (double)n * d + (double)n * n_out) * es,
-                    (double)n_dev * (4.0 * kv_dim * es + 4)));
+    CB_TRY(run_gemm(c, s, g, CB_PROF_DEV, kv_flops, kv_bytes, (double)n_dev * (4.0 * kv_dim * es + 4)));
     g.dev_out = nullptr;
     {
       ProfScope ps(c, s, CB_PROF_TOPK, 0, (double)n_dev * 4 + (double)rows * (8 + 4.0 * kv_dim * es));
@@ -360,41 +353,29 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     }
     if (rows == 0) return CB_OK;
     sel_rows = ws.sel_rows;
-    if (!q_all) {
-      g.a_rows = sel_rows; g.M = rows; g.n_seg = 1;
-      {
-        const void *wm[1] = {w->wq};
-        const float *sc[1] = {w->wq_scale};
-        const int wr[1] = {q_dim};
-        CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, d, &wv));
-      }
-      g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
-      g.row_pos = pos_out;
-      CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * rows * d * q_dim,
-                      ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es, 0));
-    }
   } else {
-    // every row is kept: one fused Q|K|V projection, K and V written straight into the cache
     {
       ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)n * 8);
       CB_HIP(hipMemcpyAsync(pos_out, row_pos, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
       if (cache_row_out)
         CB_HIP(hipMemcpyAsync(cache_row_out, crow, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
     }
-    g.a_rows = nullptr; g.M = n; g.n_seg = 3;
-    {
-      const void *wm[3] = {w->wq, w->wk, w->wv};
-      const float *sc[3] = {w->wq_scale, w->wk_scale, w->wv_scale};
-      const int wr[3] = {q_dim, kv_dim, kv_dim};
-      CB_TRY(stage_weights(c, s, ws, 3, wm, sc, wr, d, &wv));
-    }
-    g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
-    g.seg[1] = {wv.w[1], kv_dim, kc, kv_dim, crow, 1, nullptr};
-    g.seg[2] = {wv.w[2], kv_dim, vc, kv_dim, crow, 0, nullptr};
-    g.row_pos = row_pos;
-    CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * n * d * (q_dim + 2 * kv_dim),
-                    ((double)(q_dim + 2 * kv_dim) * d + (double)n * d + (double)n * (q_dim + 2 * kv_dim)) * es, 0));
+    g.seg[0] = {wv.w[0], kv_dim, kc, kv_dim, crow, 1, nullptr};
+    g.seg[1] = {wv.w[1], kv_dim, vc, kv_dim, crow, 0, nullptr};
+    CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, kv_flops, kv_bytes, 0));
   }
+  // Q of the rows that are kept (Sec. 4.2), gathered through the selection; plain bf16 operands
+  g.a_rows = sel_rows; g.M = rows; g.n_seg = 1; g.a_lo_off = 0;
+  {
+    const void *wm[1] = {w->wq};
+    const float *sc[1] = {w->wq_scale};
+    const int wr[1] = {q_dim};
+    CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, d, &wv));
+  }
+  g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
+  g.row_pos = pos_out;
+  CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * rows * d * q_dim,
+                  ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es, 0));
   {
     // attention is per request: its rows against its own cache slab -- all requests in one launch
     // through the device table (bf16), else a launch per request
@@ -408,14 +389,14 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
         total_qwg += attention_query_workgroups(segs[b].k + segs[b].S, m.n_q_heads, m.n_kv_heads);
         max_t = std::max(max_t, segs[b].T);
       }
-      CB_HIP(launch_attention(dt, ws.qbuf, q_all ? sel_rows : nullptr, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads,
+      CB_HIP(launch_attention(dt, ws.qbuf, nullptr, pos_out, rows, kc, vc, ws.obuf, m.n_q_heads,
                               m.n_kv_heads, m.head_dim, max_t, ws.partial, ws.partial_floats, s, seg_dev, n_segs,
                               total_qwg));
     }
     for (int b = 0; b < n_segs && !varlen; ++b) {
       const int rows_b = segs[b].k + segs[b].S;
-      const char *q_b = (const char *)ws.qbuf + (q_all ? 0 : (size_t)out_off * q_dim * es);
-      CB_HIP(launch_attention(dt, q_b, q_all ? sel_rows + out_off : nullptr, pos_out + out_off, rows_b,
+      const char *q_b = (const char *)ws.qbuf + (size_t)out_off * q_dim * es;
+      CB_HIP(launch_attention(dt, q_b, nullptr, pos_out + out_off, rows_b,
                               (char *)kc + (size_t)b * cache_stride * kv_dim * es,
                               (char *)vc + (size_t)b * cache_stride * kv_dim * es,
                               (char *)ws.obuf + (size_t)out_off * q_dim * es, m.n_q_heads, m.n_kv_heads,

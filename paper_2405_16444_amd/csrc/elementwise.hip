@@ -216,8 +216,9 @@ hipError_t launch_copy_rows_f32(const float *in, float *out, size_t n, hipStream
 // ---------------------------------------------------------------------------
 // RMSNorm: one block per row; the row (float) is read twice (second read hits L2).
 // With lo_off > 0 every value x is stored as the pair (hi, lo) = (T(x), T(x - hi)), lo lying
-// lo_off elements after hi: the Q/K/V projections multiply both parts, which gives them an
-// input accurate to float although the matrix cores take bf16 operands.
+// lo_off elements after hi: the K/V projection multiplies both parts, which gives it an
+// input accurate to float although the matrix cores take bf16 operands (the Q projection and
+// the MLP read the high parts only).
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h,

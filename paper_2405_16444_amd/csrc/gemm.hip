@@ -355,7 +355,7 @@ template <int I, int NB, int EPI, int NWV, bool HL = false>
 __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN), DMA_CP = BN + 4;
   constexpr int BMO = HL ? BM / 2 : BM;                  // output rows per tile
-  static_assert(!HL || EPI == EPI_SEG, "operand pairs are for the Q/K/V projections only");
+  static_assert(!HL || EPI == EPI_SEG, "operand pairs are for the K/V projection only");
   constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128, W_RING = DMA_SA * A_STAGE;
   constexpr int WN = NWV / 2;                            // wavefronts as 2 x WN
   constexpr int NBW = 2 * NB / WN;                       // 32-column blocks per wavefront

@@ -4,6 +4,7 @@
 // (vocab * d * sizeof(T) bytes), not the matrix cores.
 #include "common.h"
 #include "kernels.h"
+#include <mutex>
 
 namespace cb {
 
@@ -85,6 +86,14 @@ hipError_t launch_lm_head(int dtype, const float *h_row, const void *gain, const
   const int rows_per_wg = 4 * kHeadRowsPerWave;
   const dim3 grid((vocab + rows_per_wg - 1) / rows_per_wg);
   const size_t smem = (size_t)d * sizeof(float);
+  // d = 16384 needs 64 KB of dynamic LDS on top of the static array: above the default limit
+  static std::once_flag once;
+  std::call_once(once, [] {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_kernel<float>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&lm_head_kernel<bf16>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+  });
   if (dtype == 0)
     hipLaunchKernelGGL(lm_head_kernel<float>, grid, dim3(256), smem, s, h_row, (const float *)gain,
                        (const float *)w, d, vocab, eps, logits);

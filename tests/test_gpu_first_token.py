@@ -41,6 +41,8 @@ def run_case(P, model, n_suffix, seed, head=None):
     ("f32", 64, 7, 1),             # fewer rows than one wavefront takes
     ("bf16", 512, 4099, 3),
     ("bf16", 1024, 32, 64),
+    ("bf16", 16384, 520, 2),       # the widest model the head accepts (the normalised row fills 64 KB of LDS)
+    ("f32", 16384, 96, 1),
 ])
 def test_first_token_small(P, dtype, d, vocab, n_suffix):
     model = ModelShape(1, d, 4, 2, 64, 128, 1e-5, 1e4, dtype, vocab)

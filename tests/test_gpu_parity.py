@@ -403,3 +403,25 @@ def test_error_codes_leave_buffers_untouched(P):
     torch.cuda.synchronize()
     assert torch.equal(kg.cpu(), kc) and torch.equal(vg.cpu(), vc) and not bool(big.any())
     P.cb_destroy(ctx)
+
+
+@pytest.mark.parametrize("name", ["bf16", "f32", "bf16_g7"])
+def test_rows_in_any_order_without_selection(P, name):
+    """With every row kept nothing relies on the rows being sorted: the same rows handed over in a shuffled
+    order give the same results row by row (the attention kernels take a workgroup's key range from the
+    LARGEST position among its rows, not from its last row)."""
+    model = MODELS[name]
+    n_tokens, n_rows = 700, 333
+    announce("rows in any order", name)
+    lw, h, pos, kc, vc = layer_case(model, n_tokens, n_rows, 0, seed=8100)
+    perm = torch.randperm(n_rows, generator=torch.Generator().manual_seed(3))
+    h_p, pos_p = h[perm].contiguous(), pos[perm].contiguous()
+    h_out, pos_out, _, kg, vg = run_layer_both(P, model, lw, h_p, pos_p, kc, vc, 0, n_rows, want_dev=False)
+    assert torch.equal(pos_out, pos_p)
+    rnd = O.storage_round(model.dtype)
+    ko, vo = to_np(kc), to_np(vc)
+    nlw = np_layers([lw])[0]
+    h_ref, _, _, _ = O.fuse_layer(nlw, model, to_np(h), pos.numpy(), 0, ko, vo, n_rows, kv_round=rnd)
+    tol = TOL[model.dtype]
+    assert max_abs_rel(to_np(h_out), h_ref[perm.numpy()]) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
