@@ -70,7 +70,13 @@ def run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, want_dev):
     ("mistral7b", 3136, 359, 64, 231),        # last layer: 295 candidates -> 231
     ("mistral7b", 3136, 589, 64, 461),        # 525 rows kept (flat 15 %): the gate/up GEMM's last round of tiles is shared along K
     ("yi34b", 3136, 525, 64, 400),            # 7 query heads per kv head, d = 7168
+    ("yi34b", 3136, 282, 64, 154),            # ratio 0.05: the row count at which the weights, not the matrix cores, would bind
+    ("yi34b", 3136, 1050, 64, 922),           # ratio 0.30
     ("llama70b", 4064, 300, 64, 200),         # 8 query heads per kv head, d = 8192, d_ff = 28672
+    ("llama70b", 4064, 4064, 64, 1200),       # the headline request's layer 1: first check on all 4000 context rows
+    ("llama70b", 4064, 1264, 64, 1178),       # its layer 2: nearly every candidate survives (gradual filtering)
+    ("llama70b", 4064, 728, 64, 600),         # a middle layer
+    ("llama70b", 4064, 366, 64, 300),         # its last layer
     ("long32k", 32896, 700, 128, 500),        # 32 K-token cache: attention KV split + long positions
     ("long32k", 131200, 400, 128, 200),       # 128 K-token cache: 1025 key tiles, positions beyond 2^17
 ])
