@@ -2,15 +2,15 @@
 // selected tokens, then the ordinary attention and the rest of the layer).
 // C[M, N] = A[M, K] * W[N, K]^T with both operands K-contiguous.
 //
-// bf16 storage: v_mfma_f32_32x32x16_bf16 with float accumulation.  The main kernel
-// (gemm_bf16_dma_kernel) streams (32*I) x (64*NB) x 64 tiles through LDS rings filled by
-// direct global->LDS loads, with an XCD-aware tile order; a simpler register-staged
-// 128x128x64 kernel covers K that is not a multiple of 64.
+// bf16 storage: matrix-core MFMAs with float accumulation.  The main kernel
+// (gemm_bf16_dma_kernel, v_mfma_f32_16x16x32_bf16) streams (32*I) x (64*NB) x 64 tiles through LDS
+// rings filled by direct global->LDS loads, with an XCD-aware tile order; a simpler register-staged
+// 128x128x64 kernel (v_mfma_f32_32x32x16_bf16) covers K that is not a multiple of 64.
 // float storage: plain FMA tiles (parity mode, not tuned).
-// The SwiGLU and float-output epilogues work straight from the accumulator registers;
-// the segment epilogue parks the tile in LDS and walks it row-major, 4 adjacent columns
-// per lane, which gives the rotary embedding its (2i, 2i+1) pair in one lane and 8-byte
-// stores.  A problem with too few tiles to fill the chip is split along K: the main
+// The SwiGLU and float-output epilogues work straight from the accumulator registers (a lane
+// holds four adjacent columns of a row); the segment epilogue parks the tile in LDS and walks it
+// row-major, 4 adjacent columns per lane, which lets the two wavefront halves of an operand-pair
+// tile be added and gives the half-split rotary order its partner column.  A problem with too few tiles to fill the chip is split along K: the main
 // kernel then stores raw partial sums and a second kernel adds them in a fixed order
 // (no atomics: bitwise reproducible) and applies the epilogue.
 // Epilogues:
@@ -205,9 +205,11 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //               rows: every global request is a whole cache line)
 //   wavefronts  NWV = 4 as 2 x 2 (128-column tiles; two such workgroups share a CU when the
 //               rings fit twice) or NWV = 8 as 2 x 4 (256-column tiles: two wavefronts per
-//               SIMD, each (BM/2) x 64).  Operand reads are issued by hand (inline
-//               ds_read_b128 + explicit s_waitcnt lgkmcnt) one k-step ahead of the MFMAs
-//               that use them, slotted between those MFMAs.
+//               SIMD, each (BM/2) x 64).  A wavefront's sub-tile is cut into 16 x 16 blocks, one
+//               v_mfma_f32_16x16x32_bf16 each per 32-deep k-step.  Operand reads are issued by
+//               hand (inline ds_read_b128 + explicit s_waitcnt lgkmcnt) one half-step (half of
+//               the wavefront's rows of one k-step) ahead of the MFMAs that use them, slotted
+//               between those MFMAs.
 //   LDS rings   activation tile (BM rows x 128 bytes): 2 stages; weight tile (256 rows x
 //               128 bytes): the 3-4 stages that still fit in 160 KB -- weights stream
 //               from HBM once and need the deeper queue, activations mostly hit L2.
@@ -217,12 +219,12 @@ __device__ __forceinline__ void lds_epilogue(const float *sC, int pitch, int row
 //               row l/8, f(r) = (r&7) ^ ((r>>3)&1), so that the later 16-byte operand
 //               reads of 8 (and of 16) consecutive rows hit distinct bank groups
 //               (XOR swizzle instead of padding).
-//   pipeline    one barrier per k-tile, placed before the LAST k-step of tile t: by
+//   pipeline    one barrier per k-tile, placed before the LAST half-step of tile t: by
 //               then every wavefront holds its last fragments of stage t in
 //               registers, so after "tile t+1 landed" (s_waitcnt vmcnt) + barrier the
 //               stage is refilled with tile t+S and the first fragments of tile t+1
 //               are requested while the last MFMAs of tile t run.  The loads of a tile
-//               are spread over four k-steps (no burst on the memory pipeline).  The
+//               are spread over four half-steps (no burst on the memory pipeline).  The
 //               compiler does not order LDS reads against these loads, hence the
 //               explicit waits; plain s_barrier is used because __syncthreads()
 //               would drain every outstanding load.
@@ -279,71 +281,78 @@ __device__ __forceinline__ void xcd_tile(int j, int xcd, int tiles_m, int nblk, 
   *mt = g * kGroupM + r % gm;
 }
 
-// silu(gate) * up from one wavefront's accumulators (IH x NBW blocks of 32 x 32): blocks
-// 0..NBW/2-1 of a lane hold gate columns, blocks NBW/2..NBW-1 the same columns of the up matrix;
-// lane l holds column (l % 32) of each block and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row
-// block.  row0 / col0: first output row / column of the wavefront.
-template <int IH, int NBW>
-__device__ __forceinline__ void swiglu_from_registers(const f32x16 (&acc)[IH][NBW], const GemmParams &p,
+// silu(gate) * up from one wavefront's accumulators (RB x CB blocks of 16 x 16): blocks
+// 0..CB/2-1 of a lane hold gate columns, blocks CB/2..CB-1 the same columns of the up matrix;
+// lane l holds row (l % 16) and columns 4*(l/16) .. +3 of each block.  row0 / col0: first output
+// row / column of the wavefront.
+template <int RB, int CB>
+__device__ __forceinline__ void swiglu_from_registers(const f32x4 (&acc)[RB][CB], const GemmParams &p,
                                                       int row0, int col0, int lane) {
-  const int h = lane >> 5, ln = lane & 31;
+  const int l_row = lane & 15, l_col = (lane >> 4) * 4;
 #pragma unroll
-  for (int i = 0; i < IH; ++i) {
+  for (int i = 0; i < RB; ++i) {
+    const int gr = row0 + i * 16 + l_row;
+    if (gr >= p.M) continue;
+    bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int gr = row0 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-      if (gr >= p.M) continue;
-      bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
+    for (int jb = 0; jb < CB / 2; ++jb) {
+      const int gc = col0 + jb * 16 + l_col;
+      float o[4];
 #pragma unroll
-      for (int jb = 0; jb < NBW / 2; ++jb) {
-        const int gc = col0 + jb * 32 + ln;
-        if (gc >= p.N) continue;
-        const float gt = acc[i][jb][r], up = acc[i][jb + NBW / 2][r];
+      for (int r = 0; r < 4; ++r) {
+        const float gt = acc[i][jb][r], up = acc[i][jb + CB / 2][r];
         // silu(g) * u = g * u / (1 + 2^(-g log2 e))
         const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt);
-        orow[gc] = (bf16)(gt * up * __builtin_amdgcn_rcpf(den));
+        o[r] = gt * up * __builtin_amdgcn_rcpf(den);
+      }
+      if (gc + 3 < p.N) {
+        store4<bf16>(orow + gc, o[0], o[1], o[2], o[3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (gc + r < p.N) orow[gc + r] = (bf16)o[r];
       }
     }
   }
 }
 
 // Completes the tiles that several workgroups of the SwiGLU launch shared along K.  The partial
-// sums lie in register order: [slot][split][wavefront][row block i][column block jb][r][lane].
-// One wavefront here owns one (wavefront, i, gate block jb) unit of a tile: it adds the gate and
+// sums lie in register order: [slot][split][wavefront][16-row block i][16-column block jb][lane][4].
+// One wavefront here owns four (wavefront, i, gate block jb) units of a tile in turn: it adds the gate and
 // the up block over the splits in ascending K order and applies the epilogue.
 template <int I, int NB, int NWV>
 __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tiles_m, int tiles_n) {
-  constexpr int IH = I / 2, BM = 32 * I, BN = 64 * NB, WN = NWV / 2, NBW = 2 * NB / WN, HB = NBW / 2;
-  constexpr int UNITS = NWV * IH * HB;                    // per tile
+  constexpr int IH = I / 2, BM = 32 * I, BN = 64 * NB, WN = NWV / 2, NBW = 2 * NB / WN;
+  constexpr int RB = I, CB = 2 * NBW, HB = CB / 2;
+  constexpr int UNITS = NWV * RB * HB;                    // per tile; a multiple of 16
   const int lane = threadIdx.x & 63;
-  const int slot = blockIdx.x / (UNITS / 4);
-  const int u = (blockIdx.x % (UNITS / 4)) * 4 + (threadIdx.x >> 6);
-  const int wave = u / (IH * HB), i = (u / HB) % IH, jb = u % HB;
+  const int slot = blockIdx.x / (UNITS / 16);
   const int xcd = slot & 7, j = (p.tail_first >> 3) + (slot >> 3);
   int nt, mt;
   xcd_tile(j, xcd, tiles_m, (tiles_n + 7) >> 3, &nt, &mt);
   if (nt >= tiles_n) return;
-  const float *pg = p.partial + (size_t)slot * p.tail_splits * (BM * BN) + (size_t)wave * (IH * NBW * 16 * 64) +
-                    (size_t)(i * NBW + jb) * (16 * 64) + lane;
-  float gate[16], up[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) gate[r] = up[r] = 0.f;
-  for (int zz = 0; zz < p.tail_splits; ++zz, pg += BM * BN) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      gate[r] += pg[r * 64];
-      up[r] += pg[(HB * 16 + r) * 64];
+  const int l_row = lane & 15, l_col = (lane >> 4) * 4;
+  for (int q = 0; q < 4; ++q) {
+    const int u = ((blockIdx.x % (UNITS / 16)) * 4 + (threadIdx.x >> 6)) * 4 + q;
+    const int wave = u / (RB * HB), i = (u / HB) % RB, jb = u % HB;
+    const float *pg = p.partial + (size_t)slot * p.tail_splits * (BM * BN) + (size_t)wave * (RB * CB * 4 * 64) +
+                      (size_t)((i * CB + jb) * 64 + lane) * 4;
+    f32x4 gate = {0.f, 0.f, 0.f, 0.f}, up = {0.f, 0.f, 0.f, 0.f};
+    for (int zz = 0; zz < p.tail_splits; ++zz, pg += BM * BN) {
+      gate += *reinterpret_cast<const f32x4 *>(pg);
+      up += *reinterpret_cast<const f32x4 *>(pg + HB * 64 * 4);
     }
-  }
-  const int wm = wave / WN, wn = wave % WN, h = lane >> 5, ln = lane & 31;
-  const int gc = nt * (BN / 2) + wn * (BN / WN / 2) + jb * 32 + ln;
-  if (gc >= p.N) return;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int gr = mt * BM + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+    const int wm = wave / WN, wn = wave % WN;
+    const int gc = nt * (BN / 2) + wn * (BN / WN / 2) + jb * 16 + l_col;
+    const int gr = mt * BM + wm * IH * 32 + i * 16 + l_row;
     if (gr >= p.M) continue;
-    const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate[r]);
-    reinterpret_cast<bf16 *>(p.dst[0])[(size_t)gr * p.ld[0] + gc] = (bf16)(gate[r] * up[r] * __builtin_amdgcn_rcpf(den));
+    bf16 *orow = reinterpret_cast<bf16 *>(p.dst[0]) + (size_t)gr * p.ld[0];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if (gc + r >= p.N) continue;
+      const float den = 1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate[r]);
+      orow[gc + r] = (bf16)(gate[r] * up[r] * __builtin_amdgcn_rcpf(den));
+    }
   }
 }
 
@@ -358,11 +367,11 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   static_assert(!HL || EPI == EPI_SEG, "operand pairs are for the K/V projection only");
   constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128, W_RING = DMA_SA * A_STAGE;
   constexpr int WN = NWV / 2;                            // wavefronts as 2 x WN
-  constexpr int NBW = 2 * NB / WN;                       // 32-column blocks per wavefront
+  constexpr int NBW = 2 * NB / WN;                       // 32-column groups per wavefront
   constexpr int LA = BM / (8 * NWV), LW = BN / (8 * NWV); // 16-byte loads per lane per tile (8 rows per wavefront each)
   static_assert(SW >= 3, "the vmcnt bookkeeping below assumes at least 3 weight stages");
-  constexpr int IH = I / 2;                              // row blocks per wavefront
-  constexpr int NF = IH + NBW;                           // operand reads per k-step per wavefront
+  constexpr int IH = I / 2;                              // 32-row groups per wavefront
+  constexpr int RB = I, CB = 2 * NBW;                    // 16-row / 16-column MFMA blocks per wavefront
   constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -439,83 +448,102 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
       CB_GLDS16(src_w[i] + k0, smem + W_RING + (t % SW) * W_STAGE + (wave + NWV * i) * 1024);
   };
 
-  f32x16 acc[IH][NBW];
+  // v_mfma_f32_16x16x32_bf16 with the WEIGHT fragment as its first operand: block (i, jb) of a wavefront is
+  // 16 output rows x 16 output columns, and lane l ends up with row (l % 16), columns 4*(l/16) .. +3 of it,
+  // i.e. four adjacent output columns (one 16-byte store, one rotary pair twice over).  Of the two MFMA
+  // shapes this one sustains the higher rate on this chip once the operands are real data: the chip is
+  // power-limited then, and the 16x16 shape moves half the accumulator registers per flop.
+  f32x4 acc[RB][CB];
 #pragma unroll
-  for (int i = 0; i < IH; ++i)
+  for (int i = 0; i < RB; ++i)
 #pragma unroll
-    for (int jb = 0; jb < NBW; ++jb)
+    for (int jb = 0; jb < CB; ++jb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][jb][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][jb][r] = 0.f;
 
   if (nk > 0) {
-    const int sw = (lane & 7) ^ ((lane >> 3) & 1), h = lane >> 5;
-    int rd[4];                                                    // k-step ks reads chunk 2*ks + h
+    // A fragment is 16 rows x 32 k: lane l reads the 16-byte chunk (l / 16) of the k-step's 64 bytes of row (l % 16)
+    const int sw = (lane & 7) ^ ((lane >> 3) & 1);
+    int rd[2];                                                    // k-step ks (32 deep) reads chunk 4*ks + l/16
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) rd[ks] = (lane & 31) * 128 + (((2 * ks + h) ^ sw) << 4);
+    for (int ks = 0; ks < 2; ++ks) rd[ks] = (lane & 15) * 128 + (((4 * ks + (lane >> 4)) ^ sw) << 4);
     const int a_off = (wm * IH * 32) * 128, b_off = (wn * (BN / WN)) * 128;
-    int blk_ok = 0;                                    // bit i: row block i of this wavefront holds a real row
+    int blk_ok = 0;                                    // bit i: 16-row block i of this wavefront holds a real row
 #pragma unroll
-    for (int i = 0; i < IH; ++i) blk_ok |= (m0 + (HL ? i : wm * IH + i) * 32 < p.M) << i;
+    for (int i = 0; i < RB; ++i) blk_ok |= (m0 + (HL ? 0 : wm * IH * 32) + i * 16 < p.M) << i;
     blk_ok = __builtin_amdgcn_readfirstlane(blk_ok);
-    bf16x8 fa[2][IH], fb[2][NBW];
-    constexpr int NM = IH * NBW;                       // MFMAs per k-step per wavefront
+    // A k-tile is walked in four HALF-STEPS hs = 2*ks + h: k-step ks (32 deep), row half h (IH of the wavefront's
+    // 16-row blocks).  Activation fragments are double-buffered per half-step, weight fragments per k-step.
+    bf16x8 fa[2][IH], fb[2][CB];
+    constexpr int NM = IH * CB;                        // MFMAs per half-step per wavefront
     constexpr int NL = LA + LW;                        // loads per tile per lane
-    constexpr int NSLOT = NM > NF ? NM : NF;
-    // operand read number idx (0..NF-1) into fragment buffer buf; base_w / base_a are the LDS
-    // byte addresses of this lane's first weight / activation fragment of the k-step
-    auto read_one = [&](unsigned base_w, unsigned base_a, int buf, int idx) {
-      if (idx < NBW) {
-        switch (idx) {
-          case 0: lds_read16<0>(fb[buf][0], base_w); break;
-          case 1: if (NBW > 1) lds_read16<4096>(fb[buf][NBW > 1 ? 1 : 0], base_w); break;
-          case 2: if (NBW > 2) lds_read16<8192>(fb[buf][NBW > 2 ? 2 : 0], base_w); break;
-          default: if (NBW > 3) lds_read16<12288>(fb[buf][NBW > 3 ? 3 : 0], base_w); break;
-        }
-      } else {
-        switch (idx - NBW) {
-          case 0: lds_read16<0>(fa[buf][0], base_a); break;
-          case 1: if (IH > 1) lds_read16<4096>(fa[buf][IH > 1 ? 1 : 0], base_a); break;
-          case 2: if (IH > 2) lds_read16<8192>(fa[buf][IH > 2 ? 2 : 0], base_a); break;
-          default: if (IH > 3) lds_read16<12288>(fa[buf][IH > 3 ? 3 : 0], base_a); break;
-        }
+    constexpr int NSLOT = NM > IH + CB ? NM : IH + CB;
+    // fragment number n (16 rows each, 2 KB apart) of the operand whose first fragment this lane reads at `base`
+    auto read_frag = [&](bf16x8 &dst, unsigned base, int n) {
+      switch (n) {
+        case 0: lds_read16<0>(dst, base); break;
+        case 1: lds_read16<2048>(dst, base); break;
+        case 2: lds_read16<4096>(dst, base); break;
+        case 3: lds_read16<6144>(dst, base); break;
+        case 4: lds_read16<8192>(dst, base); break;
+        case 5: lds_read16<10240>(dst, base); break;
+        case 6: lds_read16<12288>(dst, base); break;
+        default: lds_read16<14336>(dst, base); break;
       }
     };
     const unsigned lds0 = (unsigned)(size_t)smem;
-    auto pin = [&](int buf) {
-#pragma unroll
-      for (int jb = 0; jb < NBW; ++jb) lds_pin(fb[buf][jb]);
-#pragma unroll
-      for (int i = 0; i < IH; ++i) lds_pin(fa[buf][i]);
-    };
-    // One k-step: the MFMAs of fragment buffer `buf`, with the operand reads of the next k-step
-    // (tile tn, step ksn, into the other buffer) and -- when `refill` -- the global loads of the
-    // next stages slotted in between them.  A wavefront issues in order and has its SIMD to
-    // itself, so anything not placed between two MFMAs would add to the MFMA time.
-    auto step = [&](int buf, bool next_reads, int tn, int ksn, int q0, int q1, int tl) {
-      const unsigned base_w = lds0 + W_RING + (tn % SW) * W_STAGE + b_off + rd[ksn];
-      const unsigned base_a = lds0 + (tn % DMA_SA) * A_STAGE + a_off + rd[ksn];
-#pragma unroll
-      for (int j = 0; j < NSLOT; ++j) {
-        // a 32-row block that lies wholly past the last row (only in the last row tile) is skipped:
-        // the wavefront sharing the SIMD gets the matrix core instead
-        if (j < NM && ((blk_ok >> (j / NBW)) & 1))
-          acc[j / NBW][j % NBW] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][j / NBW], fb[buf][j % NBW],
-                                                                         acc[j / NBW][j % NBW], 0, 0, 0);
-        // global loads q0 .. q1-1 of tile tl, spread evenly over the slots of this k-step
+    // One half-step hs of the current tile: its MFMAs, with the operand reads of the half-step that follows
+    // (half-step hsn of tile tn: its activation fragments, and the weight fragments too when it opens a
+    // k-step) and the global loads q0 .. q1-1 of tile tl slotted in between them.  A wavefront issues in
+    // order, so anything not placed between two MFMAs would add to the MFMA time.
+    auto step = [&](int hs, bool next_reads, int tn, int hsn, int q0, int q1, int tl) {
+      const int ab = hs & 1, bb = (hs >> 1) & 1, h = hs & 1;
+      const int nab = hsn & 1, nbb = (hsn >> 1) & 1;
+      const bool with_w = (hsn & 1) == 0;
+      const unsigned base_a = lds0 + (tn % DMA_SA) * A_STAGE + a_off + (hsn & 1) * (IH * 2048) + rd[hsn >> 1];
+      const unsigned base_w = lds0 + W_RING + (tn % SW) * W_STAGE + b_off + rd[hsn >> 1];
+      const int n_reads = next_reads ? IH + (with_w ? CB : 0) : 0;
+      // what rides along in MFMA slot j: the global loads q0 .. q1-1 of tile tl, spread evenly over the slots of
+      // this half-step, and one operand read of the next half-step
+      auto slot_work = [&](int j) {
 #pragma unroll
         for (int q = q0 + j * (q1 - q0) / NSLOT; q < q0 + (j + 1) * (q1 - q0) / NSLOT; ++q) issue_one(tl, q);
-        if (next_reads && j < NF) read_one(base_w, base_a, buf ^ 1, j);
+        if (j < n_reads) {
+          if (j < IH) read_frag(fa[nab][j], base_a, j);
+          else read_frag(fb[nbb][j - IH], base_w, j - IH);
+        }
         __builtin_amdgcn_sched_barrier(0);
+      };
+#pragma unroll
+      for (int ii = 0; ii < IH; ++ii) {
+        // a 16-row block that lies wholly past the last row (only in the last row tile) is skipped: the
+        // wavefront sharing the SIMD gets the matrix core instead.  One scalar branch per row block, not per
+        // MFMA; the loads and reads of its slots follow outside the branch, so no register is written on two paths.
+        if ((blk_ok >> (h * IH + ii)) & 1) {
+#pragma unroll
+          for (int jb = 0; jb < CB; ++jb)
+            acc[h * IH + ii][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[bb][jb], fa[ab][ii], acc[h * IH + ii][jb], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb) slot_work(ii * CB + jb);
       }
+#pragma unroll
+      for (int j = NM; j < NSLOT; ++j) slot_work(j);
       if (next_reads) {
         lds_wait<0>();
-        pin(buf ^ 1);
+#pragma unroll
+        for (int i = 0; i < IH; ++i) lds_pin(fa[nab][i]);
+        if (with_w) {
+#pragma unroll
+          for (int jb = 0; jb < CB; ++jb) lds_pin(fb[nbb][jb]);
+        }
       }
     };
 
     // Issue order: W(0..SW-2), A(0), A(1), W(SW-1) up front; from then on the loads of a tile are
-    // spread over four k-steps so that the memory pipeline never sees a burst: after the barrier
-    // of tile t (its stages are free) the first half of A(t+2); during the first three k-steps of
+    // spread over four half-steps so that the memory pipeline never sees a burst: after the barrier
+    // of tile t (its stages are free) the first half of A(t+2); during the first three half-steps of
     // tile t+1 the second half of A(t+2), then W(t+SW) in two halves.  When tile t+1 is needed,
     // the only loads that may be younger than the last load of A(t+1) are the LW loads of
     // W(t+SW-1).
@@ -529,64 +557,71 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
 #pragma unroll
     for (int q = 0; q < NL; ++q) issue_one(1, q);
 #pragma unroll
-    for (int q = 0; q < NF; ++q) read_one(lds0 + W_RING + b_off + rd[0], lds0 + a_off + rd[0], 0, q);
+    for (int q = 0; q < IH; ++q) read_frag(fa[0][q], lds0 + a_off + rd[0], q);
+#pragma unroll
+    for (int q = 0; q < CB; ++q) read_frag(fb[0][q], lds0 + W_RING + b_off + rd[0], q);
     lds_wait<0>();
-    pin(0);
+#pragma unroll
+    for (int q = 0; q < IH; ++q) lds_pin(fa[0][q]);
+#pragma unroll
+    for (int q = 0; q < CB; ++q) lds_pin(fb[0][q]);
     if (nk > 1) {
       // tile 0: tile 1 is already on its way
       step(0, true, 0, 1, 0, 0, 0);
       step(1, true, 0, 2, 0, 0, 0);
-      step(0, true, 0, 3, 0, 0, 0);
+      step(2, true, 0, 3, 0, 0, 0);
       vm_wait<LW>();
       wg_barrier();
-      step(1, true, 1, 0, 0, QA, 2);
+      step(3, true, 1, 0, 0, QA, 2);
     }
     for (int t = 1; t + 1 < nk; ++t) {
       step(0, true, t, 1, QA, LA, t + 1);
       step(1, true, t, 2, LA, QW, t + 1);
-      step(0, true, t, 3, QW, NL, t + 1);
-      // last k-step: fragments are in registers, so once tile t+1 has landed everywhere the
+      step(2, true, t, 3, QW, NL, t + 1);
+      // last half-step: its fragments are in registers, so once tile t+1 has landed everywhere the
       // stages of tile t can be refilled while these MFMAs run
       vm_wait<LW>();
       wg_barrier();
-      step(1, true, t + 1, 0, 0, QA, t + 2);
+      step(3, true, t + 1, 0, 0, QA, t + 2);
     }
     step(0, true, nk - 1, 1, 0, 0, 0);
     step(1, true, nk - 1, 2, 0, 0, 0);
-    step(0, true, nk - 1, 3, 0, 0, 0);
-    step(1, false, 0, 0, 0, 0, 0);
+    step(2, true, nk - 1, 3, 0, 0, 0);
+    step(3, false, 0, 0, 0, 0, 0);
   }
+  // Block (i, jb) of this wavefront, lane l: output row i*16 + l%16 and columns jb*16 + 4*(l/16) .. +3 of its sub-tile
+  const int l_row = lane & 15, l_col = (lane >> 4) * 4;
   if (EPI == EPI_SWIGLU && tail_z >= 0) {
-    // raw partial sums of a shared tile, in register order (each store is 256 contiguous bytes)
+    // raw partial sums of a shared tile, in register order (each store is 1 KB contiguous)
     const int slot = (j - (p.tail_first >> 3)) * 8 + xcd;
-    float *pb = p.partial + ((size_t)slot * p.tail_splits + tail_z) * (BM * BN) + (size_t)wave * (IH * NBW * 16 * 64);
+    float *pb = p.partial + ((size_t)slot * p.tail_splits + tail_z) * (BM * BN) + (size_t)wave * (RB * CB * 4 * 64);
 #pragma unroll
-    for (int i = 0; i < IH; ++i)
+    for (int i = 0; i < RB; ++i)
 #pragma unroll
-      for (int jb = 0; jb < NBW; ++jb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) pb[((i * NBW + jb) * 16 + r) * 64 + lane] = acc[i][jb][r];
+      for (int jb = 0; jb < CB; ++jb)
+        *reinterpret_cast<f32x4 *>(pb + ((i * CB + jb) * 64 + lane) * 4) = acc[i][jb];
     return;
   }
   if (EPI == EPI_SWIGLU) {
-    swiglu_from_registers<IH, NBW>(acc, p, m0 + wm * IH * 32, n0 + wn * (BN / WN / 2), lane);
+    swiglu_from_registers<RB, CB>(acc, p, m0 + wm * IH * 32, n0 + wn * (BN / WN / 2), lane);
     return;
   }
   if (EPI != EPI_SEG) {
-    // Epilogue straight from the accumulator registers: lane l holds column (l % 32) of each of
-    // its four 32-column blocks and rows 8*(r/4) + 4*(l/32) + r%4 of each 32-row block.
-    const int h = lane >> 5, ln = lane & 31;
+    // raw sums straight from the accumulator registers, four adjacent columns per lane
 #pragma unroll
-    for (int i = 0; i < IH; ++i) {
+    for (int i = 0; i < RB; ++i) {
+      const int gr = m0 + wm * IH * 32 + i * 16 + l_row;
+      if (gr >= p.M) continue;
+      float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int gr = m0 + (wm * IH + i) * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        if (gr >= p.M) continue;
-        float *prow = p.partial + ((size_t)z * p.M + gr) * p.N;
+      for (int jb = 0; jb < CB; ++jb) {
+        const int gc = n0 + wn * (BN / WN) + jb * 16 + l_col;
+        if (gc + 3 < p.N) {
+          *reinterpret_cast<f32x4 *>(prow + gc) = acc[i][jb];
+        } else {
 #pragma unroll
-        for (int jb = 0; jb < NBW; ++jb) {
-          const int gc = n0 + wn * (BN / WN) + jb * 32 + ln;
-          if (gc < p.N) prow[gc] = acc[i][jb][r];
+          for (int r = 0; r < 4; ++r)
+            if (gc + r < p.N) prow[gc + r] = acc[i][jb][r];
         }
       }
     }
@@ -602,16 +637,13 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     for (int part = 0; part < 2; ++part) {
       if (wm == part) {
 #pragma unroll
-        for (int i = 0; i < IH; ++i)
+        for (int i = 0; i < RB; ++i)
 #pragma unroll
-          for (int jb = 0; jb < NBW; ++jb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int row = i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-              const int col = wn * (BN / WN) + jb * 32 + (lane & 31);
-              if (part == 0) sC[row * DMA_CP + col] = acc[i][jb][r];
-              else sC[row * DMA_CP + col] += acc[i][jb][r];
-            }
+          for (int jb = 0; jb < CB; ++jb) {
+            f32x4 *dst = reinterpret_cast<f32x4 *>(sC + (i * 16 + l_row) * DMA_CP + wn * (BN / WN) + jb * 16 + l_col);
+            if (part == 0) *dst = acc[i][jb];
+            else *dst += acc[i][jb];
+          }
       }
       __syncthreads();
     }
@@ -622,25 +654,20 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   constexpr int PASSES = (I + 3) / 4;
 #pragma unroll
   for (int ps = 0; ps < PASSES; ++ps) {
-    const int i0 = ps * 4;                                   // first row block of the pass
-    const int nb = (I - i0) < 4 ? (I - i0) : 4;
+    const int i0 = ps * 8;                                   // first 16-row block of the pass
+    const int nb = (2 * I - i0) < 8 ? (2 * I - i0) : 8;
     if (ps > 0) __syncthreads();
 #pragma unroll
-    for (int i = 0; i < IH; ++i) {
-      const int ib = wm * IH + i;                            // this wavefront's row block
-      if (ib >= i0 && ib < i0 + 4) {
+    for (int i = 0; i < RB; ++i) {
+      const int ib = wm * RB + i;                            // this wavefront's 16-row block within the tile
+      if (ib >= i0 && ib < i0 + 8) {
 #pragma unroll
-        for (int jb = 0; jb < NBW; ++jb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = (ib - i0) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-            const int col = wn * (BN / WN) + jb * 32 + (lane & 31);
-            sC[row * DMA_CP + col] = acc[i][jb][r];
-          }
+        for (int jb = 0; jb < CB; ++jb)
+          *reinterpret_cast<f32x4 *>(sC + ((ib - i0) * 16 + l_row) * DMA_CP + wn * (BN / WN) + jb * 16 + l_col) = acc[i][jb];
       }
     }
     __syncthreads();
-    lds_epilogue<bf16, EPI, BN>(sC, DMA_CP, nb * 32, m0 + i0 * 32, n0, z, p);
+    lds_epilogue<bf16, EPI, BN>(sC, DMA_CP, nb * 16, m0 + i0 * 16, n0, z, p);
   }
 }
 
