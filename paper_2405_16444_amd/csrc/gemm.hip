@@ -956,21 +956,21 @@ static int pick_row_blocks(int M) {
 // Tile shape and K split of the direct-to-LDS kernel for the Q/K/V, output and down projections,
 // from a cost model in microseconds fitted to a sweep of every (tile, split) pair over the
 // projection shapes of the 7B- and 70B-shaped workloads (row counts 295 .. 1264) on the chip:
-//   main launch   = rounds x t_full x k-tiles per workgroup + 8.5 (launch, pipeline fill, epilogue)
+//   main launch   = rounds x t_full x k-tiles per workgroup + 9.9 (launch, pipeline fill, epilogue)
 //   t_full        = time of one 64-deep k-tile with every slot of the chip busy (a slot = one resident
 //                   workgroup: two per CU for the tiles whose rings fit twice into LDS, else one)
 //   partial round = runs faster per tile, because fewer workgroups share the chip's power and its
 //                   L2 -> LDS paths: t_full x (1 - relief x (1 - fill))
-//   finish launch = 2.5 + 0.285 us per MB of parked sums (splits x M x N floats)
-// The model's choice is within 0 .. 9 % (mean 2 %) of the best measured pair on every shape of the sweep.
+//   finish launch = 2.3 + 0.258 us per MB of parked sums (splits x M x N floats)
+// The model's choice is within 0 .. 5 % (mean 1 %) of the best measured pair on every shape of the sweep.
 // max_splits caps the split (scratch the caller can spare); parked: a finish launch runs anyway.
 struct DmaShape { int I, NB; double t_full; };
-static const DmaShape kDmaShapes[] = {{2, 2, 0.80}, {4, 2, 1.28}, {6, 2, 1.02}, {8, 2, 1.27},
-                                      {4, 4, 1.19}, {6, 4, 1.57}, {8, 4, 1.96}};
+static const DmaShape kDmaShapes[] = {{2, 2, 0.80}, {4, 2, 1.23}, {6, 2, 1.02}, {8, 2, 1.28},
+                                      {4, 4, 1.14}, {6, 4, 1.54}, {8, 4, 1.90}};
 
 static void pick_dma_plan(int M, int N, int K, int max_splits, bool parked, size_t out_elems, GemmPlan *pl) {
   const int k_tiles = K / DMA_BK;
-  const double park_us = (double)out_elems * 4.0e-6 * 0.285;   // per split
+  const double park_us = (double)out_elems * 4.0e-6 * 0.258;   // per split
   double best = 1e30;
   for (const DmaShape &c : kDmaShapes) {
     if (c.I == 2 && M > 64) continue;
@@ -982,9 +982,9 @@ static void pick_dma_plan(int M, int N, int K, int max_splits, bool parked, size
       const long wgs = tiles * sp;
       const long full = wgs / slots;
       const double last = (double)(wgs - full * slots) / slots;          // fill of the last round
-      const double relief = slots == 512 ? 0.69 : 0.50;
+      const double relief = slots == 512 ? 0.69 : 0.45;
       const double per_tile = full * c.t_full + (last > 0 ? c.t_full * (1.0 - relief + relief * last) : 0.0);
-      const double cost = per_tile * ceil_div(k_tiles, sp) + 8.5 + (sp > 1 || parked ? sp * park_us + 2.5 : 0.0);
+      const double cost = per_tile * ceil_div(k_tiles, sp) + 9.9 + (sp > 1 || parked ? sp * park_us + 2.3 : 0.0);
       if (cost < best - 1e-9) { best = cost; pl->I = c.I; pl->NB = c.NB; pl->splits = sp; }
     }
   }
