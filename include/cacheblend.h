@@ -63,9 +63,11 @@ typedef enum { CB_ROPE_ADJACENT = 0, CB_ROPE_HALF = 1 } cb_rope_layout;
  *   CB_W_NATIVE  elements of storage type T
  *   CB_W_INT8    int8 elements q with one float scale per OUTPUT feature (row of the [out, in]
  *                matrix): w[o][i] = q[o][i] * scale[o].  Needs dtype == CB_BF16.  Arithmetic stays
- *                bf16 x bf16 -> float on the matrix cores: a projection's weights are expanded to
- *                bf16 (rounded to nearest even) into the workspace right before it runs, so HBM holds
- *                one byte per weight and the workspace one projection's worth of bf16.
+ *                bf16 x bf16 -> float on the matrix cores.  A projection whose input width is a multiple
+ *                of 64 reads the bytes itself: they travel as bytes through HBM, L2 and LDS, are expanded
+ *                to bf16 in registers (exact: |q| <= 128) and the float sums are multiplied by scale[o].
+ *                Any other input width: the matrix is expanded to bf16(q * scale) into the workspace right
+ *                before its projection runs.  Either way HBM holds one byte per weight.
  * Norm gains, the final norm and the vocabulary matrix of cb_first_token are always of type T. */
 typedef enum { CB_W_NATIVE = 0, CB_W_INT8 = 1 } cb_weight_format;
 

@@ -120,18 +120,18 @@ int xn_pitch(const cb_ctx *c) { return c->m.d_model + xn_lo_off(c); }
 size_t partial_floats_needed(const cb_ctx *c, int max_rows) {
   const cb_model_desc &m = c->m;
   const int d = m.d_model, q_dim = m.n_q_heads * m.head_dim, kv_dim = m.n_kv_heads * m.head_dim;
-  const int rh = m.rope_layout == CB_ROPE_HALF, hl = xn_lo_off(c) > 0;
+  const int rh = m.rope_layout == CB_ROPE_HALF, hl = xn_lo_off(c) > 0, w8 = m.weight_format == CB_W_INT8;
   std::vector<size_t> &memo = c->partial_memo;
   if (memo.empty()) memo.push_back(0);
   while ((int)memo.size() <= max_rows) {
     const int M = (int)memo.size();
     size_t need = memo.back();
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 1, rh, m.head_dim));   // K|V, checked
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 0, rh, m.head_dim));   // K|V, every row kept
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim, d, 0, 0, rh, m.head_dim));         // Q
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, q_dim, 0, 0, 0, 0));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, m.d_ff, 0, 0, 0, 0));
-    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, M, m.d_ff, d, 0, 0, 0, 0));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 1, rh, m.head_dim, w8));   // K|V, checked
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, 2 * kv_dim, d, hl, 0, rh, m.head_dim, w8));   // K|V, every row kept
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SEG, M, q_dim, d, 0, 0, rh, m.head_dim, w8));         // Q
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, q_dim, 0, 0, 0, 0, w8));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_F32, M, d, m.d_ff, 0, 0, 0, 0, w8));
+    need = std::max(need, gemm_partial_floats(m.dtype, EPI_SWIGLU, M, m.d_ff, d, 0, 0, 0, 0, w8));
     // the attention KV split borrows the same scratch (the two are never live together)
     need = std::max(need, attention_partial_floats_bound(m.dtype, M, m.n_q_heads, m.n_kv_heads, m.head_dim));
     memo.push_back(need);
@@ -162,9 +162,15 @@ LayerWs carve_layer(const cb_ctx *c, char *base, int R) {
   w.partial = (float *)take(w.partial_floats * 4);
   w.dev = (float *)take((size_t)R * 4);
   w.sel_rows = (int32_t *)take((size_t)R * 4);
-  // the widest projection (gate and up together, or Q, K and V together) expanded to bf16
-  const size_t stage = m.weight_format == CB_W_INT8
-                           ? std::max((size_t)2 * m.d_ff, q_dim + 2 * kv_dim) * m.d_model * 2 : 0;
+  // int8 weights that the projection kernels cannot read themselves: room for the widest such projection
+  // (gate and up together, or K and V together) expanded to bf16
+  size_t stage = 0;
+  if (m.weight_format == CB_W_INT8) {
+    const int dt = m.dtype == CB_BF16 ? 1 : 0;
+    if (!gemm_int8_in_kernel(dt, m.d_model)) stage = std::max((size_t)2 * m.d_ff, q_dim + 2 * kv_dim) * m.d_model * 2;
+    if (!gemm_int8_in_kernel(dt, (int)q_dim)) stage = std::max(stage, q_dim * m.d_model * 2);
+    if (!gemm_int8_in_kernel(dt, m.d_ff)) stage = std::max(stage, (size_t)m.d_ff * m.d_model * 2);
+  }
   w.wstage = take(stage);
   w.bytes = off;
   return w;
@@ -218,14 +224,21 @@ int check_layer_args(const cb_ctx *c, int layer, const cb_layer_weights *w, int 
   return CB_OK;
 }
 
-// The matrices a projection launch reads.  Native weights: the caller's pointers.  int8 weights:
-// each matrix is expanded to bf16 into the staging area first (one after the other, so that the
-// matrices of one launch lie side by side) and the launch reads the expansion.
-struct WeightView { const void *w[3]; };
+// The matrices a projection launch reads.  Native weights: the caller's pointers.  int8 weights: the
+// projection kernel reads them itself (scale non-NULL) wherever it can -- bf16 storage and an input width
+// that is a multiple of 64 --; otherwise each matrix is expanded to the storage type into the staging area
+// first (one after the other, so that the matrices of one launch lie side by side) and the launch reads
+// the expansion.
+struct WeightView { const void *w[3]; const float *scale[3]; };
 int stage_weights(cb_ctx *c, hipStream_t s, const LayerWs &ws, int n, const void *const *w,
                   const float *const *scale, const int *rows, int cols, WeightView *out) {
+  for (int i = 0; i < 3; ++i) out->scale[i] = nullptr;
   if (c->m.weight_format != CB_W_INT8) {
     for (int i = 0; i < n; ++i) out->w[i] = w[i];
+    return CB_OK;
+  }
+  if (gemm_int8_in_kernel(c->m.dtype == CB_BF16 ? 1 : 0, cols)) {
+    for (int i = 0; i < n; ++i) { out->w[i] = w[i]; out->scale[i] = scale[i]; }
     return CB_OK;
   }
   size_t off = 0, bytes = 0;
@@ -316,8 +329,8 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
   g.row_pos = row_pos;
   const double kv_flops = 2.0 * n * d * 2 * kv_dim, kv_bytes = ((double)2 * kv_dim * d + (double)n * d + (double)n * 2 * kv_dim) * es;
   if (check) {
-    g.seg[0] = {wv.w[0], kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1, kc};
-    g.seg[1] = {wv.w[1], kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0, vc};
+    g.seg[0] = {wv.w[0], kv_dim, ws.kvnew, 2 * kv_dim, nullptr, 1, kc, wv.scale[0]};
+    g.seg[1] = {wv.w[1], kv_dim, (char *)ws.kvnew + (size_t)kv_dim * es, 2 * kv_dim, nullptr, 0, vc, wv.scale[1]};
     float *dev = dev_out ? dev_out : ws.dev;
     // one request: its candidates are the leading rows; several: every row gets a value (a
     // suffix row's is never looked at)
@@ -360,8 +373,8 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
       if (cache_row_out)
         CB_HIP(hipMemcpyAsync(cache_row_out, crow, (size_t)n * 4, hipMemcpyDeviceToDevice, s));
     }
-    g.seg[0] = {wv.w[0], kv_dim, kc, kv_dim, crow, 1, nullptr};
-    g.seg[1] = {wv.w[1], kv_dim, vc, kv_dim, crow, 0, nullptr};
+    g.seg[0] = {wv.w[0], kv_dim, kc, kv_dim, crow, 1, nullptr, wv.scale[0]};
+    g.seg[1] = {wv.w[1], kv_dim, vc, kv_dim, crow, 0, nullptr, wv.scale[1]};
     CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, kv_flops, kv_bytes, 0));
   }
   // Q of the rows that are kept (Sec. 4.2), gathered through the selection; plain bf16 operands
@@ -372,7 +385,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     const int wr[1] = {q_dim};
     CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, d, &wv));
   }
-  g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr};
+  g.seg[0] = {wv.w[0], q_dim, ws.qbuf, q_dim, nullptr, 1, nullptr, wv.scale[0]};
   g.row_pos = pos_out;
   CB_TRY(run_gemm(c, s, g, CB_PROF_REDUCE, 2.0 * rows * d * q_dim,
                   ((double)q_dim * d + (double)rows * d + (double)rows * q_dim) * es, 0));
@@ -413,7 +426,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     const int wr[1] = {d};
     CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, q_dim, &wv));
   }
-  f.seg[0].w = wv.w[0]; f.seg[0].n = d;
+  f.seg[0].w = wv.w[0]; f.seg[0].w_scale = wv.scale[0]; f.seg[0].n = d;
   f.out_f32 = ws.hmid; f.resid = h_in; f.resid_rows = sel_rows;
   f.norm_gain = w->mlp_norm; f.norm_out = ws.xn2; f.norm_ld = d; f.norm_lo_off = 0; f.norm_eps = m.rms_eps;
   f.partial = ws.partial; f.partial_floats = ws.partial_floats;
@@ -427,8 +440,8 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     const int wr[2] = {F, F};
     CB_TRY(stage_weights(c, s, ws, 2, wm, sc, wr, d, &wv));
   }
-  u.seg[0] = {wv.w[0], F, ws.act, F, nullptr, 0, nullptr};
-  u.seg[1] = {wv.w[1], F, nullptr, 0, nullptr, 0, nullptr};
+  u.seg[0] = {wv.w[0], F, ws.act, F, nullptr, 0, nullptr, wv.scale[0]};
+  u.seg[1] = {wv.w[1], F, nullptr, 0, nullptr, 0, nullptr, wv.scale[1]};
   u.partial = ws.partial; u.partial_floats = ws.partial_floats;
   CB_TRY(run_gemm(c, s, u, CB_PROF_REDUCE, 2.0 * rows * d * 2 * F,
                   ((double)2 * F * d + (double)rows * d + (double)rows * F) * es, 0));
@@ -439,7 +452,7 @@ int fuse_layer_impl(cb_ctx *c, const cb_layer_weights *w, const float *h_in, con
     const int wr[1] = {d};
     CB_TRY(stage_weights(c, s, ws, 1, wm, sc, wr, F, &wv));
   }
-  f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = wv.w[0];
+  f.a = ws.act; f.lda = F; f.K = F; f.seg[0].w = wv.w[0]; f.seg[0].w_scale = wv.scale[0];
   f.out_f32 = h_out; f.resid = ws.hmid; f.resid_rows = nullptr;
   f.norm_gain = next_gain; f.norm_out = ws.xn; f.norm_ld = xld; f.norm_lo_off = lo_off;
   CB_TRY(run_gemm(c, s, f, CB_PROF_REDUCE, 2.0 * rows * F * d, ((double)F * d + (double)rows * F) * es,

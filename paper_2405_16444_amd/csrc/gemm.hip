@@ -34,6 +34,8 @@ struct GemmParams {
   int M, K, N;          // N: total output columns (EPI_SWIGLU: d_ff)
   int n_seg;
   const void *w[3];
+  const float *w_scale[3];   // non-NULL (direct-to-LDS kernel only): w[i] holds int8 values and output column c of
+                             // segment i is w_scale[i][c] times the sum over them
   int nb[4];            // column boundaries of the segments
   void *dst[3];
   int ld[3];
@@ -72,19 +74,20 @@ struct GemmParams {
 };
 
 // weight row that feeds tile column gc (clamped into range)
+// (es: elements of T per weight element, for byte-addressed callers)
 template <typename T, int EPI>
-__device__ __forceinline__ const T *weight_row(const GemmParams &p, int gc, int half_bn, int n0, int c) {
+__device__ __forceinline__ const T *weight_row(const GemmParams &p, int gc, int half_bn, int n0, int c, int es = 1) {
   if (EPI == EPI_SWIGLU) {
     // tile columns [0, half) come from the gate matrix, [half, 2*half) from the up matrix
     int which = c >= half_bn;
     int row = min(n0 + (which ? c - half_bn : c), p.N - 1);
-    return reinterpret_cast<const T *>(p.w[which]) + (size_t)row * p.K;
+    return reinterpret_cast<const T *>(p.w[which]) + (size_t)row * p.K * es;
   }
   gc = min(gc, p.N - 1);
   int s = 0;
   if (p.n_seg > 1 && gc >= p.nb[1]) s = 1;
   if (p.n_seg > 2 && gc >= p.nb[2]) s = 2;
-  return reinterpret_cast<const T *>(p.w[s]) + (size_t)(gc - p.nb[s]) * p.K;
+  return reinterpret_cast<const T *>(p.w[s]) + (size_t)(gc - p.nb[s]) * p.K * es;
 }
 
 template <typename T> __device__ __forceinline__ float4 load4(const T *s);
@@ -239,13 +242,18 @@ constexpr int DMA_BK = 64;
 // Two rings: the activation tile (mostly L2 hits) is double-buffered, the weight tile (streamed
 // from HBM, long latency) gets every remaining stage that fits in 160 KB, up to 4.
 constexpr int DMA_SA = 2;
-constexpr int dma_w_stages(int I, int BN) {
-  if (BN == 128 && I <= 4) return 3;                   // <= 80 KB: two workgroups per CU
+// w8: int8 weights, 64 bytes per weight row and stage instead of 128, so up to 6 stages fit.
+constexpr int dma_w_stages(int I, int BN, bool w8 = false) {
+  const int stage = BN * (w8 ? 64 : 128), cap = w8 ? 6 : 4;
+  if (BN == 128 && I <= 4) {                           // <= 80 KB: two workgroups per CU
+    const int n = (80 * 1024 - DMA_SA * 32 * I * 128) / stage;
+    return w8 ? (n > cap ? cap : n) : 3;
+  }
   const int left = 160 * 1024 - DMA_SA * 32 * I * 128;
-  return left / (BN * 128) > 4 ? 4 : left / (BN * 128);
+  return left / stage > cap ? cap : left / stage;
 }
-constexpr int dma_smem_bytes(int I, int BN) {
-  const int ring = DMA_SA * 32 * I * 128 + dma_w_stages(I, BN) * BN * 128;
+constexpr int dma_smem_bytes(int I, int BN, bool w8 = false) {
+  const int ring = DMA_SA * 32 * I * 128 + dma_w_stages(I, BN, w8) * BN * (w8 ? 64 : 128);
   const int park = (I < 4 ? 32 * I : 128) * (BN + 4) * 4;
   return ring > park ? ring : park;
 }
@@ -258,6 +266,17 @@ constexpr int dma_smem_bytes(int I, int BN) {
 // lds_wait<N>() (N = number of younger reads that may still be in flight).
 template <int OFF> __device__ __forceinline__ void lds_read16(bf16x8 &dst, unsigned addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+template <int OFF> __device__ __forceinline__ void lds_read8(u32x2 &dst, unsigned addr) {
+  asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+// eight int8 weights -> the bf16 MFMA fragment (exact: |value| <= 128 needs 8 significant bits)
+__device__ __forceinline__ bf16x8 int8x8_to_bf16(u32x2 q) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (bf16)(float)(int)(signed char)(q[e >> 2] >> (8 * (e & 3)));
+  return r;
 }
 template <int N> __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N)); }
 // ties a fragment to the preceding wait so that no use of it is scheduled before the wait
@@ -360,15 +379,19 @@ __global__ __launch_bounds__(256) void swiglu_tail_kernel(GemmParams p, int tile
 // BM/2 logical rows twice -- their high parts in its first half, their low parts in its second --
 // so the wavefronts with wm = 0 multiply the high parts and those with wm = 1 the low parts of the
 // SAME output rows, and the two sets of sums are added in LDS before the epilogue.
-template <int I, int NB, int EPI, int NWV, bool HL = false>
+// W8: the weights are int8 (one byte per element in memory and in LDS, half the traffic of both); a fragment
+// is expanded to bf16 in registers right before its k-step and the per-column scales multiply the finished sums.
+template <int I, int NB, int EPI, int NWV, bool HL = false, bool W8 = false>
 __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
-  constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN), DMA_CP = BN + 4;
+  constexpr int BM = 32 * I, BN = 64 * NB, SW = dma_w_stages(I, BN, W8), DMA_CP = BN + 4;
+  constexpr int WE = W8 ? 1 : 2;                         // bytes per weight element
   constexpr int BMO = HL ? BM / 2 : BM;                  // output rows per tile
   static_assert(!HL || EPI == EPI_SEG, "operand pairs are for the K/V projection only");
-  constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128, W_RING = DMA_SA * A_STAGE;
+  constexpr int A_STAGE = BM * 128, W_STAGE = BN * 64 * WE, W_RING = DMA_SA * A_STAGE;
   constexpr int WN = NWV / 2;                            // wavefronts as 2 x WN
   constexpr int NBW = 2 * NB / WN;                       // 32-column groups per wavefront
-  constexpr int LA = BM / (8 * NWV), LW = BN / (8 * NWV); // 16-byte loads per lane per tile (8 rows per wavefront each)
+  constexpr int LA = BM / (8 * NWV), LW = W_STAGE / (1024 * NWV);   // 16-byte loads per lane per tile (1 KB per wavefront each)
+  static_assert(LW >= 2 && LW % 2 == 0, "the load schedule issues a weight tile in two halves");
   static_assert(SW >= 3, "the vmcnt bookkeeping below assumes at least 3 weight stages");
   constexpr int IH = I / 2;                              // 32-row groups per wavefront
   constexpr int RB = I, CB = 2 * NBW;                    // 16-row / 16-column MFMA blocks per wavefront
@@ -403,7 +426,8 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   const int nk = (ke - kb) / DMA_BK;
 
   // global source of each of this lane's loads per tile (row pointer + swizzled chunk)
-  const bf16 *src_a[LA], *src_w[LW];
+  const bf16 *src_a[LA];
+  const char *src_w[LW];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
     const int r = (wave + NWV * i) * 8 + (lane >> 3);         // row of the activation tile
@@ -415,19 +439,21 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   }
 #pragma unroll
   for (int i = 0; i < LW; ++i) {
-    const int r = (wave + NWV * i) * 8 + (lane >> 3);         // row of the weight tile
-    const int chunk = (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
-    const bf16 *wrow;
+    // a wavefront-wide load brings 1 KB: 8 rows of 128 bytes, or 16 rows of 64 bytes of int8 weights, whose four
+    // 16-byte chunks are swizzled by f8(r) = (r >> 2) & 3 (the 8-byte fragment reads of 16 rows then hit 64 banks)
+    const int r = W8 ? (wave + NWV * i) * 16 + (lane >> 2) : (wave + NWV * i) * 8 + (lane >> 3);   // row of the weight tile
+    const int chunk = W8 ? (lane & 3) ^ ((r >> 2) & 3) : (lane & 7) ^ ((r & 7) ^ ((r >> 3) & 1));
+    const char *wrow;
     if (EPI == EPI_SWIGLU) {
       // each wavefront's half of the tile columns holds its gate columns followed by the SAME
       // up columns, so that a lane ends up with gate and up of one output element
       constexpr int WC = BN / WN, HC = WC / 2;         // columns per wavefront / per operand
       const int which = (r % WC) / HC, oc = min(n0 + (r / WC) * HC + (r % HC), p.N - 1);
-      wrow = reinterpret_cast<const bf16 *>(p.w[which]) + (size_t)oc * p.K;
+      wrow = reinterpret_cast<const char *>(p.w[which]) + (size_t)oc * p.K * WE;
     } else {
-      wrow = weight_row<bf16, EPI>(p, n0 + r, BN / 2, n0, r);
+      wrow = reinterpret_cast<const char *>(weight_row<char, EPI>(p, n0 + r, BN / 2, n0, r, WE));
     }
-    src_w[i] = wrow + chunk * 8 + kb;
+    src_w[i] = wrow + chunk * 16 + kb * WE;
   }
   // load number idx of tile t: idx < LA activation, else weight; tile indices are clamped so
   // that every tile issues the same number of loads
@@ -438,14 +464,14 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     } else {
       const int tw = t + SW - DMA_SA;                 // the weight ring runs SW - 2 tiles further ahead
       const int k0 = min(tw, nk - 1) * DMA_BK;
-      CB_GLDS16(src_w[idx - LA] + k0, smem + W_RING + (tw % SW) * W_STAGE + (wave + NWV * (idx - LA)) * 1024);
+      CB_GLDS16(src_w[idx - LA] + k0 * WE, smem + W_RING + (tw % SW) * W_STAGE + (wave + NWV * (idx - LA)) * 1024);
     }
   };
   auto issue_w = [&](int t) {
     const int k0 = min(t, nk - 1) * DMA_BK;
 #pragma unroll
     for (int i = 0; i < LW; ++i)
-      CB_GLDS16(src_w[i] + k0, smem + W_RING + (t % SW) * W_STAGE + (wave + NWV * i) * 1024);
+      CB_GLDS16(src_w[i] + k0 * WE, smem + W_RING + (t % SW) * W_STAGE + (wave + NWV * i) * 1024);
   };
 
   // v_mfma_f32_16x16x32_bf16 with the WEIGHT fragment as its first operand: block (i, jb) of a wavefront is
@@ -474,11 +500,31 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     blk_ok = __builtin_amdgcn_readfirstlane(blk_ok);
     // A k-tile is walked in four HALF-STEPS hs = 2*ks + h: k-step ks (32 deep), row half h (IH of the wavefront's
     // 16-row blocks).  Activation fragments are double-buffered per half-step, weight fragments per k-step.
-    bf16x8 fa[2][IH], fb[2][CB];
+    // (int8 weights: the raw 8-byte fragments of the next k-step wait in fq and are expanded into fb[0] as the
+    // k-step begins, each right before the first MFMA that uses it)
+    bf16x8 fa[2][IH], fb[W8 ? 1 : 2][CB];
+    u32x2 fq[W8 ? CB : 1];
+    int rd8[2];                                        // int8 weights: 8 bytes of row (l % 16), k-step ks, k group l / 16
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+      rd8[ks] = (lane & 15) * 64 + (((2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3)) << 4) + ((lane >> 4) & 1) * 8;
+    const int b_off8 = (wn * (BN / WN)) * 64;
     constexpr int NM = IH * CB;                        // MFMAs per half-step per wavefront
     constexpr int NL = LA + LW;                        // loads per tile per lane
     constexpr int NSLOT = NM > IH + CB ? NM : IH + CB;
     // fragment number n (16 rows each, 2 KB apart) of the operand whose first fragment this lane reads at `base`
+    auto read_wq = [&](u32x2 &dst, unsigned base, int n) {     // int8 weight fragment n (16 rows, 1 KB apart)
+      switch (n) {
+        case 0: lds_read8<0>(dst, base); break;
+        case 1: lds_read8<1024>(dst, base); break;
+        case 2: lds_read8<2048>(dst, base); break;
+        case 3: lds_read8<3072>(dst, base); break;
+        case 4: lds_read8<4096>(dst, base); break;
+        case 5: lds_read8<5120>(dst, base); break;
+        case 6: lds_read8<6144>(dst, base); break;
+        default: lds_read8<7168>(dst, base); break;
+      }
+    };
     auto read_frag = [&](bf16x8 &dst, unsigned base, int n) {
       switch (n) {
         case 0: lds_read16<0>(dst, base); break;
@@ -497,11 +543,11 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
     // k-step) and the global loads q0 .. q1-1 of tile tl slotted in between them.  A wavefront issues in
     // order, so anything not placed between two MFMAs would add to the MFMA time.
     auto step = [&](int hs, bool next_reads, int tn, int hsn, int q0, int q1, int tl) {
-      const int ab = hs & 1, bb = (hs >> 1) & 1, h = hs & 1;
-      const int nab = hsn & 1, nbb = (hsn >> 1) & 1;
+      const int ab = hs & 1, bb = W8 ? 0 : (hs >> 1) & 1, h = hs & 1;
+      const int nab = hsn & 1, nbb = W8 ? 0 : (hsn >> 1) & 1;
       const bool with_w = (hsn & 1) == 0;
       const unsigned base_a = lds0 + (tn % DMA_SA) * A_STAGE + a_off + (hsn & 1) * (IH * 2048) + rd[hsn >> 1];
-      const unsigned base_w = lds0 + W_RING + (tn % SW) * W_STAGE + b_off + rd[hsn >> 1];
+      const unsigned base_w = lds0 + W_RING + (tn % SW) * W_STAGE + (W8 ? b_off8 + rd8[hsn >> 1] : b_off + rd[hsn >> 1]);
       const int n_reads = next_reads ? IH + (with_w ? CB : 0) : 0;
       // what rides along in MFMA slot j: the global loads q0 .. q1-1 of tile tl, spread evenly over the slots of
       // this half-step, and one operand read of the next half-step
@@ -510,10 +556,25 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
         for (int q = q0 + j * (q1 - q0) / NSLOT; q < q0 + (j + 1) * (q1 - q0) / NSLOT; ++q) issue_one(tl, q);
         if (j < n_reads) {
           if (j < IH) read_frag(fa[nab][j], base_a, j);
+          else if (W8) read_wq(fq[j - IH], base_w, j - IH);
           else read_frag(fb[nbb][j - IH], base_w, j - IH);
         }
         __builtin_amdgcn_sched_barrier(0);
       };
+      if (W8 && h == 0) {
+        // a k-step begins with int8 weights: its fragments are expanded one at a time, each while the MFMAs of
+        // the fragment before it run, so this half-step walks the blocks column by column
+#pragma unroll
+        for (int jb = 0; jb < CB; ++jb) {
+          fb[0][jb] = int8x8_to_bf16(fq[jb]);
+#pragma unroll
+          for (int ii = 0; ii < IH; ++ii) {
+            if ((blk_ok >> ii) & 1)
+              acc[ii][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[0][jb], fa[ab][ii], acc[ii][jb], 0, 0, 0);
+            slot_work(jb * IH + ii);
+          }
+        }
+      } else {
 #pragma unroll
       for (int ii = 0; ii < IH; ++ii) {
         // a 16-row block that lies wholly past the last row (only in the last row tile) is skipped: the
@@ -528,6 +589,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
 #pragma unroll
         for (int jb = 0; jb < CB; ++jb) slot_work(ii * CB + jb);
       }
+      }
 #pragma unroll
       for (int j = NM; j < NSLOT; ++j) slot_work(j);
       if (next_reads) {
@@ -536,7 +598,10 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
         for (int i = 0; i < IH; ++i) lds_pin(fa[nab][i]);
         if (with_w) {
 #pragma unroll
-          for (int jb = 0; jb < CB; ++jb) lds_pin(fb[nbb][jb]);
+          for (int jb = 0; jb < CB; ++jb) {
+            if (W8) asm volatile("" : "+v"(fq[jb]));
+            else lds_pin(fb[nbb][jb]);
+          }
         }
       }
     };
@@ -559,12 +624,18 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
 #pragma unroll
     for (int q = 0; q < IH; ++q) read_frag(fa[0][q], lds0 + a_off + rd[0], q);
 #pragma unroll
-    for (int q = 0; q < CB; ++q) read_frag(fb[0][q], lds0 + W_RING + b_off + rd[0], q);
+    for (int q = 0; q < CB; ++q) {
+      if (W8) read_wq(fq[q], lds0 + W_RING + b_off8 + rd8[0], q);
+      else read_frag(fb[0][q], lds0 + W_RING + b_off + rd[0], q);
+    }
     lds_wait<0>();
 #pragma unroll
     for (int q = 0; q < IH; ++q) lds_pin(fa[0][q]);
 #pragma unroll
-    for (int q = 0; q < CB; ++q) lds_pin(fb[0][q]);
+    for (int q = 0; q < CB; ++q) {
+      if (W8) asm volatile("" : "+v"(fq[q]));
+      else lds_pin(fb[0][q]);
+    }
     if (nk > 1) {
       // tile 0: tile 1 is already on its way
       step(0, true, 0, 1, 0, 0, 0);
@@ -591,6 +662,31 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   }
   // Block (i, jb) of this wavefront, lane l: output row i*16 + l%16 and columns jb*16 + 4*(l/16) .. +3 of its sub-tile
   const int l_row = lane & 15, l_col = (lane >> 4) * 4;
+  if (W8) {
+    // the sums are over integer weights: scale every output column
+#pragma unroll
+    for (int jb = 0; jb < CB; ++jb) {
+      f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+      if (EPI == EPI_SWIGLU) {
+        const int gc = n0 + wn * (BN / WN / 2) + (jb % (CB / 2)) * 16 + l_col;
+        const float *ps = p.w_scale[jb / (CB / 2)];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (gc + r < p.N) sc[r] = ps[gc + r];
+      } else {
+        const int gc = n0 + wn * (BN / WN) + jb * 16 + l_col;
+        int sg = 0;
+        if (p.n_seg > 1 && gc >= p.nb[1]) sg = 1;
+        if (p.n_seg > 2 && gc >= p.nb[2]) sg = 2;
+        const float *ps = p.w_scale[sg] - p.nb[sg];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (gc + r < p.N) sc[r] = ps[gc + r];
+      }
+#pragma unroll
+      for (int i = 0; i < RB; ++i) acc[i][jb] *= sc;
+    }
+  }
   if (EPI == EPI_SWIGLU && tail_z >= 0) {
     // raw partial sums of a shared tile, in register order (each store is 1 KB contiguous)
     const int slot = (j - (p.tail_first >> 3)) * 8 + xcd;
@@ -934,6 +1030,7 @@ struct GemmPlan {
   int tail_first, tail_splits, tail_k_per_split;   // EPI_SWIGLU tail sharing (tail_splits <= 1: none)
   long grid_ids;                                   // kind 2: workgroups of the main launch
   int xcd_split;                                   // kind 2: splits dealt to XCDs (see GemmParams)
+  int w8;                                          // kind 2: int8 weights read by the kernel itself
   int raw;                                         // sums are parked in `partial` and a finish launch completes them
   size_t partial_floats;
   bool bad;                                        // needs scratch the caller did not give
@@ -968,14 +1065,14 @@ struct DmaShape { int I, NB; double t_full; };
 static const DmaShape kDmaShapes[] = {{2, 2, 0.80}, {4, 2, 1.23}, {6, 2, 1.02}, {8, 2, 1.28},
                                       {4, 4, 1.14}, {6, 4, 1.54}, {8, 4, 1.90}};
 
-static void pick_dma_plan(int M, int N, int K, int max_splits, bool parked, size_t out_elems, GemmPlan *pl) {
+static void pick_dma_plan(int M, int N, int K, int max_splits, bool parked, size_t out_elems, bool w8, GemmPlan *pl) {
   const int k_tiles = K / DMA_BK;
   const double park_us = (double)out_elems * 4.0e-6 * 0.258;   // per split
   double best = 1e30;
   for (const DmaShape &c : kDmaShapes) {
     if (c.I == 2 && M > 64) continue;
     const int bm = 32 * c.I, bn = 64 * c.NB;
-    const int slots = dma_smem_bytes(c.I, bn) <= 80 * 1024 ? 512 : 256;
+    const int slots = dma_smem_bytes(c.I, bn, w8) <= 80 * 1024 ? 512 : 256;
     const long tiles = (long)ceil_div(M, bm) * ceil_div(N, bn);
     for (int sp = 1; sp <= 16 && sp <= max_splits; ++sp) {
       if (sp > 1 && k_tiles / sp < 4) break;
@@ -996,12 +1093,16 @@ static bool needs_raw_partial(int dtype, int epi, int rope_half, int head_dim) {
   return dtype == 0 && epi == EPI_SEG && rope_half && head_dim > BN32;
 }
 
+bool gemm_int8_in_kernel(int dtype, int K) { return dtype == 1 && K % DMA_BK == 0; }
+
 // Shape of one problem.  hl: (high, low) activation pairs; force_raw: the caller wants the finish
 // launch (deviation, or the float output's residual + norm); scratch_floats: what `partial` holds
 // (the K split is capped by it; SIZE_MAX when sizing).
 static GemmPlan make_plan(int dtype, int epi, int M, int N, int K, int hl, int force_raw, int rope_half,
-                          int head_dim, size_t scratch_floats) {
+                          int head_dim, size_t scratch_floats, bool w8 = false) {
   GemmPlan pl = {};
+  pl.w8 = w8;
+  if (w8 && !gemm_int8_in_kernel(dtype, K)) pl.bad = true;
   pl.splits = 1;
   pl.hl = hl && dtype == 1 && epi == EPI_SEG;
   pl.raw = force_raw || epi == EPI_F32 || needs_raw_partial(dtype, epi, rope_half, head_dim);
@@ -1024,7 +1125,7 @@ static GemmPlan make_plan(int dtype, int epi, int M, int N, int K, int hl, int f
   } else {
     pl.kind = 2; pl.bk = DMA_BK;
     // with operand pairs the activation tile holds every output row twice
-    pick_dma_plan(pl.hl ? 2 * M : M, N, K, max_splits, pl.raw, mn, &pl);
+    pick_dma_plan(pl.hl ? 2 * M : M, N, K, max_splits, pl.raw, mn, w8, &pl);
   }
   if (pl.kind == 2) {
     pl.nwv = (pl.NB == 4 && pl.I >= 4) ? 8 : 4;
@@ -1092,9 +1193,10 @@ static int problem_n(const GemmArgs &g) {
 }
 
 size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int hl, int force_raw, int rope_half,
-                           int head_dim) {
+                           int head_dim, int w8) {
   if (M <= 0) return 0;
-  return make_plan(dtype, epi, M, N, K, hl, force_raw, rope_half, head_dim, SIZE_MAX).partial_floats;
+  return make_plan(dtype, epi, M, N, K, hl, force_raw, rope_half, head_dim, SIZE_MAX,
+                   w8 && gemm_int8_in_kernel(dtype, K)).partial_floats;
 }
 
 static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
@@ -1104,7 +1206,7 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   p.n_seg = g.epi == EPI_SEG ? g.n_seg : 1;
   p.nb[0] = 0;
   for (int i = 0; i < 3; ++i) {
-    p.w[i] = g.seg[i].w; p.dst[i] = g.seg[i].dst; p.ld[i] = g.seg[i].ld_dst;
+    p.w[i] = g.seg[i].w; p.w_scale[i] = g.seg[i].w_scale; p.dst[i] = g.seg[i].dst; p.ld[i] = g.seg[i].ld_dst;
     p.row_map[i] = g.seg[i].row_map; p.rope[i] = g.seg[i].rope;
     p.nb[i + 1] = p.nb[i] + (i < p.n_seg ? g.seg[i].n : 0);
     p.dev_cache[i] = g.dev_out ? g.seg[i].dev_cache : nullptr;
@@ -1116,8 +1218,12 @@ static GemmPlan fill_params(const GemmArgs &g, GemmParams *pp) {
   p.dev_out = g.dev_out; p.n_dev = g.n_dev; p.dev_row = g.dev_row;
   p.norm_gain = g.norm_gain; p.norm_out = g.norm_out; p.norm_ld = g.norm_ld; p.norm_lo_off = g.norm_lo_off;
   p.norm_eps = g.norm_eps;
-  const GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K, g.a_lo_off > 0, g.dev_out != nullptr, g.rope_half,
-                                g.head_dim, g.partial ? g.partial_floats : 0);
+  GemmPlan pl = make_plan(g.dtype, g.epi, g.M, p.N, g.K, g.a_lo_off > 0, g.dev_out != nullptr, g.rope_half,
+                          g.head_dim, g.partial ? g.partial_floats : 0, g.seg[0].w_scale != nullptr);
+  // every matrix of a launch is in the same format
+  const int n_w = g.epi == EPI_SEG ? g.n_seg : (g.epi == EPI_SWIGLU ? 2 : 1);
+  for (int i = 1; i < n_w; ++i)
+    if ((g.seg[i].w_scale != nullptr) != (g.seg[0].w_scale != nullptr)) pl.bad = true;
   p.a_lo_off = pl.hl ? g.a_lo_off : 0;
   p.raw_partial = pl.raw;
   p.splits = pl.splits;
@@ -1146,6 +1252,13 @@ bool gemm_needs_finish(const GemmArgs &g) {
 
 template <int I, int NB, int EPI, int NWV, bool HL = false>
 static void launch_dma(const GemmPlan &pl, const GemmParams &p, hipStream_t s) {
+  if (pl.w8) {
+    constexpr int smem = dma_smem_bytes(I, 64 * NB, true);
+    CB_LDS_LIMIT_ONCE((&gemm_bf16_dma_kernel<I, NB, EPI, NWV, HL, true>), smem);
+    hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI, NWV, HL, true>), dim3((unsigned)pl.grid_ids), dim3(64 * NWV),
+                       smem, s, p, pl.tiles_m, pl.tiles_n);
+    return;
+  }
   constexpr int smem = dma_smem_bytes(I, 64 * NB);
   CB_LDS_LIMIT_ONCE((&gemm_bf16_dma_kernel<I, NB, EPI, NWV, HL>), smem);
   hipLaunchKernelGGL((gemm_bf16_dma_kernel<I, NB, EPI, NWV, HL>), dim3((unsigned)pl.grid_ids), dim3(64 * NWV), smem,

@@ -64,6 +64,8 @@ struct GemmSeg {
   const int32_t *row_map;  // EPI_SEG: destination row = row_map[r] (NULL: r)
   int rope;                // EPI_SEG: rotate adjacent column pairs by row_pos[r]
   const void *dev_cache;   // EPI_SEG with dev_out: cache [*, n] this segment's new values are compared with (NULL: none)
+  const float *w_scale;    // non-NULL: w holds int8 values [n, K] and output column c is w_scale[c] times the sum over
+                           // them; only where gemm_int8_in_kernel() says so, and for every matrix of a launch or none
 };
 struct GemmArgs {
   int dtype;
@@ -100,10 +102,14 @@ struct GemmArgs {
 };
 // Floats of scratch a problem of this shape parks its sums in when the scratch is not the limit
 // (0 when the main kernel finishes the outputs itself); N is the total number of output columns
-// (d_ff for EPI_SWIGLU); hl: (high, low) activation pairs; force_raw: a deviation is wanted.
+// (d_ff for EPI_SWIGLU); hl: (high, low) activation pairs; force_raw: a deviation is wanted; w8: int8
+// weights (read by the kernel itself where it can).
 // For workspace sizing.
+// whether the projection kernels read int8 weights themselves for this storage type and K (else the caller
+// expands them to the storage type first)
+bool gemm_int8_in_kernel(int dtype, int K);
 size_t gemm_partial_floats(int dtype, int epi, int M, int N, int K, int hl, int force_raw, int rope_half,
-                           int head_dim);
+                           int head_dim, int w8 = 0);
 // Main kernel.  EPI_F32 problems, problems with a deviation, and problems split along K
 // (gemm_needs_finish) leave raw sums in g.partial and must be completed by launch_gemm_finish on
 // the same stream.  EPI_F32 and deviation problems REQUIRE partial_floats >= M * N.

@@ -1,7 +1,9 @@
 """8-bit projection weights (Sec. 7.1 serves the two larger models with 8-bit weights; the scheme --
 weight-only symmetric int8, one scale per output feature -- is this build's reading, "parity unpinned"
-by the paper).  The oracle dequantises (w = q * scale) and runs its ordinary definitions; the HIP path
-expands each projection's weights to bf16 right before the projection runs."""
+by the paper).  The oracle dequantises (w = q * scale) and runs its ordinary definitions; the HIP
+projection kernels read the int8 weights themselves, multiply the exact integers on the matrix cores and
+scale the finished sums (input widths that are multiples of 64), or fall back to expanding a matrix to
+bf16 right before its projection (any other width)."""
 from dataclasses import replace
 
 import numpy as np
@@ -17,6 +19,8 @@ from test_gpu_parity import BF16_M, layer_case
 
 pytestmark = pytest.mark.gpu
 INT8_M = replace(BF16_M, weight_format="int8")           # d = 512, 8 / 2 heads of 128, SwiGLU 1408
+# SwiGLU width 1392 is no multiple of 64: the down projection takes the expand-first fallback
+INT8_M_ODD = replace(INT8_M, d_ff=1392)
 
 
 @pytest.fixture(scope="module")
@@ -29,14 +33,16 @@ def np_int8_layer(lw8):
     return O.dequantize_int8({k: synth.to_f64(v) for k, v in lw8.items()})
 
 
+@pytest.mark.parametrize("model8", [INT8_M, INT8_M_ODD], ids=["ff1408", "ff1392"])
 @pytest.mark.parametrize("n_tokens,n_rows,n_suffix,k_keep", [(700, 700, 44, 197), (700, 260, 44, 216), (419, 150, 9, 141)])
-def test_int8_layer_matches_oracle_on_dequantised_weights(P, n_tokens, n_rows, n_suffix, k_keep):
-    announce("int8 layer", n_tokens, n_rows, n_suffix, k_keep)
-    lw, h, pos, kc, vc = layer_case(BF16_M, n_tokens, n_rows, n_suffix, seed=7000 + n_rows)
+def test_int8_layer_matches_oracle_on_dequantised_weights(P, model8, n_tokens, n_rows, n_suffix, k_keep):
+    announce("int8 layer", model8.d_ff, n_tokens, n_rows, n_suffix, k_keep)
+    native = replace(model8, weight_format="native")
+    lw, h, pos, kc, vc = layer_case(native, n_tokens, n_rows, n_suffix, seed=7000 + n_rows)
     lw8 = synth.quantize_int8(lw)
     n_cand = n_rows - n_suffix
     check = k_keep < n_cand
-    ctx = P.cb_create(INT8_M, n_tokens)
+    ctx = P.cb_create(model8, n_tokens)
     kg, vg = kc.cuda().contiguous(), vc.cuda().contiguous()
     h_out, pos_out, dev = P.cb_fuse_layer(ctx, 0, dev_layers([lw8])[0], h.cuda(), pos.cuda(), n_suffix, kg, vg, k_keep,
                                           want_dev=check)
@@ -46,7 +52,7 @@ def test_int8_layer_matches_oracle_on_dequantised_weights(P, n_tokens, n_rows, n
         sel_pos = pos.numpy()[:n_cand][O.top_k_indices(dev.cpu().numpy(), k_keep)]
         assert np.array_equal(pos_out.cpu().numpy()[:k_keep], sel_pos)
     ko, vo = to_np(kc), to_np(vc)
-    h_ref, pos_ref, dev_ref, _ = O.fuse_layer(np_int8_layer(lw8), INT8_M, to_np(h), pos.numpy(), n_suffix, ko, vo, k_keep,
+    h_ref, pos_ref, dev_ref, _ = O.fuse_layer(np_int8_layer(lw8), model8, to_np(h), pos.numpy(), n_suffix, ko, vo, k_keep,
                                               forced_sel=sel_pos, kv_round=O.round_bf16)
     tol = TOL["bf16"]
     assert np.array_equal(pos_out.cpu().numpy(), pos_ref)
@@ -55,18 +61,22 @@ def test_int8_layer_matches_oracle_on_dequantised_weights(P, n_tokens, n_rows, n
     assert max_abs_rel(to_np(kg.cpu()), ko) < tol and max_abs_rel(to_np(vg.cpu()), vo) < tol
     assert max_abs_rel(to_np(h_out.cpu()), h_ref) < tol
 
-    # the 8-bit path IS the bf16 path on the expanded weights bf16(q * scale): bitwise the same outputs
+    # against the bf16 path on the expanded weights bf16(q * scale): the same computation up to the rounding of
+    # the expansion (the 8-bit path multiplies the exact integers and scales the float sums)
     lw_exp = {}
     for name, t in lw8.items():
         if name.endswith("_scale"):
             continue
         lw_exp[name] = (t.float() * lw8[name + "_scale"][:, None]).to(torch.bfloat16) if t.dtype == torch.int8 else t
-    ctx2 = P.cb_create(BF16_M, n_tokens)
+    ctx2 = P.cb_create(native, n_tokens)
     kg2, vg2 = kc.cuda().contiguous(), vc.cuda().contiguous()
+    forced = None if not check else torch.from_numpy(sel_pos.astype(np.int32)).cuda()
     h2, p2, d2 = P.cb_fuse_layer(ctx2, 0, dev_layers([lw_exp])[0], h.cuda(), pos.cuda(), n_suffix, kg2, vg2, k_keep,
-                                 want_dev=check)
+                                 want_dev=check, forced_sel=forced)
     torch.cuda.synchronize()
-    assert torch.equal(h2, h_out) and torch.equal(p2, pos_out) and torch.equal(kg2, kg) and torch.equal(vg2, vg)
+    assert torch.equal(p2, pos_out)
+    assert max_abs_rel(to_np(h2.cpu()), to_np(h_out.cpu())) < tol
+    assert max_abs_rel(to_np(kg2.cpu()), to_np(kg.cpu())) < tol and max_abs_rel(to_np(vg2.cpu()), to_np(vg.cpu())) < tol
     P.cb_destroy(ctx)
     P.cb_destroy(ctx2)
 
