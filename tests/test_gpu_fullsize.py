@@ -103,6 +103,38 @@ def test_selective_layer_at_real_width(P, name, n_tokens, n_rows, n_suffix, k_ke
     assert err < tol
 
 
+@pytest.mark.parametrize("name,n_tokens,n_rows,n_suffix,k_keep", [
+    ("mistral7b", 3136, 589, 64, 461),        # gate/up tiles shared along K, int8 tiles of every projection
+    ("yi34b", 3136, 525, 64, 400),            # d = 7168: 28 column tiles of 256, 7 query heads per kv head
+    ("llama70b", 4064, 728, 64, 600),         # the 8-bit headline variant's middle layer
+    ("llama70b", 4064, 300, 64, 200),         # few rows: the small row tiles with the deep int8 weight ring
+])
+def test_selective_layer_at_real_width_with_8bit_weights(P, name, n_tokens, n_rows, n_suffix, k_keep):
+    """The projection kernels reading int8 weights themselves (Sec. 7.1's 8-bit serving), in the tile shapes
+    the real widths select; the oracle runs its ordinary definitions on the dequantised weights."""
+    w = WORKLOADS[name]
+    model = replace(w.model, n_layers=1, weight_format="int8")
+    announce("8-bit selective layer at real width", name, n_tokens, n_rows, n_suffix, k_keep)
+    lw, _ = full_layer(name)
+    lw8 = synth.quantize_int8(lw)
+    nlw8 = O.dequantize_int8({k: synth.to_f64(v) for k, v in lw8.items()})
+    h, pos, kc, vc = case(model, n_tokens, n_rows, n_suffix, seed=7300 + n_rows)
+    h_out, pos_out, dev, kg, vg = run_gpu(P, model, lw8, h, pos, kc, vc, n_suffix, k_keep, True)
+    tol = TOL["bf16"]
+    n_cand = n_rows - n_suffix
+    sel_pos = pos.numpy()[:n_cand][O.top_k_indices(dev.numpy(), k_keep)]
+    assert np.array_equal(pos_out.numpy()[:k_keep], sel_pos)                 # bit-exact selection
+    ko, vo = to_np(kc), to_np(vc)
+    h_ref, pos_ref, dev_ref, _ = O.fuse_layer(nlw8, model, to_np(h), pos.numpy(), n_suffix, ko, vo, k_keep,
+                                              forced_sel=sel_pos, kv_round=O.round_bf16)
+    del nlw8
+    assert max_abs_rel(dev.numpy(), dev_ref) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    err = max_abs_rel(to_np(h_out), h_ref)
+    print(f"{name} 8-bit: h_out max-abs-rel {err:.2e}")
+    assert err < tol
+
+
 def _bench_schedule_shapes():
     """(layer, rows in, kept) of layers 1..31 of the default benchmark request: the rows that enter
     a layer are the context rows the layer before kept, plus the 64 query rows."""
