@@ -397,7 +397,10 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
   constexpr int RB = I, CB = 2 * NBW;                    // 16-row / 16-column MFMA blocks per wavefront
   constexpr int OUT_COLS = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // scalar, so that the LDS targets of the loads are computed on the scalar unit: a vector instruction of one
+  // wavefront does not overlap the MFMAs of the other wavefront on its SIMD, it costs matrix-core time
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;              // 2 x WN wavefronts, (BM/2) x (BN/WN) each
 
   // XCD-aware tile order
@@ -498,6 +501,17 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
 #pragma unroll
     for (int i = 0; i < RB; ++i) blk_ok |= (m0 + (HL ? 0 : wm * IH * 32) + i * 16 < p.M) << i;
     blk_ok = __builtin_amdgcn_readfirstlane(blk_ok);
+    // one scalar flag per block, re-read through an empty asm at every test: left alone the compiler hoists the
+    // tests out of the loop as lane masks and rebuilds their complements with vector instructions inside it
+    // (14 of the 48 vector instructions the loop had per k-tile; with these two changes it has 16)
+    int row_ok[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) row_ok[i] = (blk_ok >> i) & 1;
+    auto block_ok = [&](int i) {
+      int v = row_ok[i];
+      asm volatile("" : "+s"(v));
+      return v != 0;
+    };
     // A k-tile is walked in four HALF-STEPS hs = 2*ks + h: k-step ks (32 deep), row half h (IH of the wavefront's
     // 16-row blocks).  Activation fragments are double-buffered per half-step, weight fragments per k-step.
     // (int8 weights: the raw 8-byte fragments of the next k-step wait in fq and are expanded into fb[0] as the
@@ -569,7 +583,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
           fb[0][jb] = int8x8_to_bf16(fq[jb]);
 #pragma unroll
           for (int ii = 0; ii < IH; ++ii) {
-            if ((blk_ok >> ii) & 1)
+            if (block_ok(ii))
               acc[ii][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[0][jb], fa[ab][ii], acc[ii][jb], 0, 0, 0);
             slot_work(jb * IH + ii);
           }
@@ -580,7 +594,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_dma_kernel(GemmParams p, i
         // a 16-row block that lies wholly past the last row (only in the last row tile) is skipped: the
         // wavefront sharing the SIMD gets the matrix core instead.  One scalar branch per row block, not per
         // MFMA; the loads and reads of its slots follow outside the branch, so no register is written on two paths.
-        if ((blk_ok >> (h * IH + ii)) & 1) {
+        if (block_ok(h * IH + ii)) {
 #pragma unroll
           for (int jb = 0; jb < CB; ++jb)
             acc[h * IH + ii][jb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[bb][jb], fa[ab][ii], acc[h * IH + ii][jb], 0, 0, 0);
