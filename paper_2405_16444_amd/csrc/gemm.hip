@@ -1031,6 +1031,69 @@ __global__ __launch_bounds__(256) void resid_norm_finish_kernel(GemmParams p) {
   }
 }
 
+// The same for rows of at most 1024 NC elements, with the row held in registers: a workgroup per row
+// is little work in flight, so the loop above runs at the latency of one load after the other (its
+// store may alias the next iteration's loads, which therefore wait for it).  Here every load of a
+// split is issued before the first sum, two splits at a time, and the second pass reads no memory.
+// Same order of additions per element as above.
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void resid_norm_finish_row_kernel(GemmParams p) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const int rr = p.resid_rows ? p.resid_rows[r] : r;
+  const size_t row = (size_t)r * p.N, stride = (size_t)p.M * p.N;
+  const int c0 = threadIdx.x * 4;
+  float4 q[NC], acc[NC];
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int c = c0 + i * 1024;
+    acc[i] = make_float4(0, 0, 0, 0);
+    q[i] = make_float4(0, 0, 0, 0);
+    if (p.resid && c < p.N) q[i] = *reinterpret_cast<const float4 *>(p.resid + (size_t)rr * p.N + c);
+  }
+#pragma unroll 2
+  for (int z = 0; z < p.splits; ++z) {
+    float4 v[NC];
+    const float *src = p.partial + z * stride + row;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int c = c0 + i * 1024;
+      v[i] = c < p.N ? *reinterpret_cast<const float4 *>(src + c) : make_float4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      acc[i].x += v[i].x; acc[i].y += v[i].y; acc[i].z += v[i].z; acc[i].w += v[i].w;
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int c = c0 + i * 1024;
+    if (p.resid) { acc[i].x += q[i].x; acc[i].y += q[i].y; acc[i].z += q[i].z; acc[i].w += q[i].w; }
+    if (c < p.N) *reinterpret_cast<float4 *>(p.out_f32 + row + c) = acc[i];
+    // the expression of the stand-alone norm kernel: a layer normalised there and one normalised here agree bitwise
+    ss += acc[i].x * acc[i].x + acc[i].y * acc[i].y + acc[i].z * acc[i].z + acc[i].w * acc[i].w;
+  }
+  if (p.norm_gain == nullptr) return;      // uniform
+  ss = block_sum_256(ss, red);
+  const float inv = 1.0f / sqrtf(ss / (float)p.N + p.norm_eps);
+  const T *gain = reinterpret_cast<const T *>(p.norm_gain);
+  T *nrow = reinterpret_cast<T *>(p.norm_out) + (size_t)r * p.norm_ld;
+#pragma unroll
+  for (int i = 0; i < NC; ++i) {
+    const int c = c0 + i * 1024;
+    if (c >= p.N) continue;
+    const float4 gn = load4<T>(gain + c);
+    const float x[4] = {acc[i].x * inv * gn.x, acc[i].y * inv * gn.y, acc[i].z * inv * gn.z, acc[i].w * inv * gn.w};
+    float hi[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) hi[e] = to_f32(from_f32<T>(x[e]));
+    store4<T>(nrow + c, x[0], x[1], x[2], x[3]);
+    if (p.norm_lo_off > 0)
+      store4<T>(nrow + p.norm_lo_off + c, x[0] - hi[0], x[1] - hi[1], x[2] - hi[2], x[3] - hi[3]);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Host side: choice of kernel, tile height and K split; launches.
 // ---------------------------------------------------------------------------
@@ -1349,8 +1412,17 @@ hipError_t launch_gemm_finish(const GemmArgs &g, hipStream_t s) {
     if (g.dtype == 0) hipLaunchKernelGGL(seg_finish_kernel<float>, grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(seg_finish_kernel<bf16>, grid, dim3(256), 0, s, p);
   } else {
-    if (g.dtype == 0) hipLaunchKernelGGL(resid_norm_finish_kernel<float>, grid, dim3(256), 0, s, p);
+#define CB_ROW(NC_)                                                                                        \
+  do {                                                                                                     \
+    if (g.dtype == 0) hipLaunchKernelGGL((resid_norm_finish_row_kernel<float, NC_>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((resid_norm_finish_row_kernel<bf16, NC_>), grid, dim3(256), 0, s, p);          \
+  } while (0)
+    if (p.N <= 2048) CB_ROW(2);
+    else if (p.N <= 4096) CB_ROW(4);
+    else if (p.N <= 8192) CB_ROW(8);
+    else if (g.dtype == 0) hipLaunchKernelGGL(resid_norm_finish_kernel<float>, grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL(resid_norm_finish_kernel<bf16>, grid, dim3(256), 0, s, p);
+#undef CB_ROW
   }
   return hipGetLastError();
 }
