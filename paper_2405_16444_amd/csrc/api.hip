@@ -912,6 +912,9 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
 
   std::vector<Seg> segs(B);
   for (int b = 0; b < B; ++b) segs[b] = {T[b], n_suffix[b], 0, T[b]};
+  // phase marks as in the one-request call: the full first layer, then the selective layers
+  ProfScope *phase = new (std::nothrow) ProfScope(c, s, CB_PROF_PHASE_FIRST, 0, 0);
+  struct PhaseGuard { ProfScope *&p; ~PhaseGuard() { delete p; } } phase_guard{phase};
   for (int l = 0; l < L; ++l) {
     for (int b = 0; b < B; ++b) segs[b].k = keep_counts[(size_t)b * L + l];
     int st = fuse_layer_impl(c, &layers[l], h_cur, p_cur, r_cur, segs.data(), B, (size_t)cache_stride,
@@ -931,6 +934,10 @@ int cb_fuse_prefill_batched(cb_ctx *c, const cb_layer_weights *layers, int32_t n
     std::swap(h_cur, h_nxt);
     std::swap(p_cur, p_nxt);
     std::swap(r_cur, r_nxt);
+    if (l == 0) {
+      delete phase;
+      phase = L > 1 ? new (std::nothrow) ProfScope(c, s, CB_PROF_PHASE_SELECTIVE, 0, 0) : nullptr;
+    }
   }
   {
     ProfScope ps(c, s, CB_PROF_OTHER, 0, (double)total_suffix * d * 8);
