@@ -151,3 +151,32 @@ def test_batch_of_one_equals_the_single_request_entry_bitwise(P):
     assert torch.equal(single.final_hidden, out.final_hidden)
     for l in range(model.n_layers):
         assert torch.equal(kg[l], kc[l]) and torch.equal(vg[l], vc[l])
+
+
+def test_batched_call_records_both_phases_and_every_kernel_class(P):
+    """The per-class profile of a batched call covers the same classes as the one-request call and
+    its two phase marks (first layer, selective layers) are non-empty and add up to at most the call."""
+    model = replace(MODELS["bf16"], n_layers=3)
+    announce("batched, profile phases")
+    layers, npl, reqs = make_requests(model, [((150, 97), 21, (1.0, 0.35, 0.15)), ((80, 120), 9, (1.0, 0.5, 0.2))], seed=91)
+    stride = max(r["w"].n_tokens for r in reqs)
+    B, L = len(reqs), model.n_layers
+    dt = synth.storage_dtype(model)
+    ctx = P.cb_create(model, stride)
+    x = torch.cat([r["x"] for r in reqs]).cuda().contiguous()
+    kc = [torch.zeros((B * stride, model.n_kv_heads, model.head_dim), dtype=dt, device="cuda") for _ in range(L)]
+    vc = [torch.zeros_like(k) for k in kc]
+    args = (ctx, dev_layers(layers), x, [r["w"].chunk_lens for r in reqs], [r["w"].n_suffix for r in reqs], kc, vc,
+            stride, [r["keep"] for r in reqs])
+    P.cb_fuse_prefill_batched(*args)
+    P.cb_profile_enable(ctx, True)
+    P.cb_fuse_prefill_batched(*args)
+    torch.cuda.synchronize()
+    prof = P.cb_profile_read(ctx)
+    P.cb_destroy(ctx)
+    first, sel = prof["phase_first_layer"]["ms"], prof["phase_selective_layers"]["ms"]
+    assert first > 0 and sel > 0
+    for cls in ("gemm", "attention", "topk", "finish"):
+        assert prof[cls]["launches"] > 0 and prof[cls]["ms"] > 0
+    per_class = sum(v["ms"] for k, v in prof.items() if not k.startswith("phase_"))
+    assert per_class <= (first + sel) * 1.05 + 0.1      # every launch lies inside one of the two phases
