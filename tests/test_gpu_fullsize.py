@@ -236,3 +236,28 @@ def test_three_layer_prefill_at_real_width(P):
     err = max_abs_rel(to_np(out.final_hidden.cpu()), ref.final_hidden)
     print(f"three layers at real width: final hidden max-abs-rel {err:.2e}")
     assert err < tol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_with_rows_wider_than_the_finish_kernel_keeps_in_registers(P, dtype):
+    """d_model = 9216: the launches that finish the float outputs (sum of the K splits + residual +
+    RMSNorm) hold rows of up to 8192 elements in registers and take their loop form beyond that."""
+    from workloads.configs import ModelShape
+    model = ModelShape(1, 9216, 8, 2, 128, 2048, 1e-5, 1e4, dtype)
+    n_tokens, n_rows, n_suffix, k_keep = 300, 140, 12, 70
+    announce("wide rows", dtype)
+    lw = synth.layer_weights(model, 1, 4242)
+    nlw = np_layers([lw])[0]
+    h, pos, kc, vc = case(model, n_tokens, n_rows, n_suffix, seed=9216)
+    h_out, pos_out, dev, kg, vg = run_gpu(P, model, lw, h, pos, kc, vc, n_suffix, k_keep, True)
+    tol = TOL[dtype]
+    sel_pos = pos.numpy()[:n_rows - n_suffix][O.top_k_indices(dev.numpy(), k_keep)]
+    assert np.array_equal(pos_out.numpy()[:k_keep], sel_pos)
+    ko, vo = to_np(kc), to_np(vc)
+    h_ref, pos_ref, dev_ref, _ = O.fuse_layer(nlw, model, to_np(h), pos.numpy(), n_suffix, ko, vo, k_keep,
+                                              forced_sel=sel_pos, kv_round=O.round_bf16 if dtype == "bf16" else O.identity)
+    assert max_abs_rel(dev.numpy(), dev_ref) < tol
+    assert max_abs_rel(to_np(kg), ko) < tol and max_abs_rel(to_np(vg), vo) < tol
+    err = max_abs_rel(to_np(h_out), h_ref)
+    print(f"d_model 9216 {dtype}: h_out max-abs-rel {err:.2e}")
+    assert err < tol
